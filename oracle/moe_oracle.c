@@ -1,0 +1,315 @@
+/*
+ * moe_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * Plain, slow, double-precision CPU statement of the gated Mixture-of-Experts
+ * layer of the DICE paper and of its token-level Conditional Communication.
+ * Only tests, the smoke check and the benchmark's cpu_baseline leg may call
+ * this file; the GPU library shares no code, header, table or constant with it.
+ *
+ * What each function follows:
+ *   router / top-K / scores  : Algorithm 1 ("[s, idx] <- router(x)"), the
+ *                              Conditional Communication figure caption
+ *                              ("K is the number of activated experts per token")
+ *   dispatch                 : Algorithm 1 ("x_d <- all2all_dispatch(x, idx)");
+ *                              on one device that is a grouping of token copies
+ *                              by destination expert
+ *   expert                   : Algorithm 1 ("x_e <- expert(x_d)"); experts are
+ *                              feed-forward networks (expert-parallelism figure)
+ *   combine + scale          : Algorithm 1 ("x_c <- all2all_combine(x_e)",
+ *                              "x <- scale(x_c, s)") and the sum
+ *                              y_i = sum_e s_i^e h_i^e of Section 4.3
+ *   refresh mask             : Algorithm 4 (Conditional Communication)
+ *   which score scales a reused h : supplement, "Expert Score Scaling"
+ *
+ * Readings where the paper is silent (all listed in the design document):
+ * softmax over all E experts without renormalisation unless asked; selection on
+ * logits, ties to the lower expert id; expert = W2 . gelu(W1 . x + b1) + b2 with
+ * the exact erf GELU; the cache is keyed by (token, slot).
+ *
+ * Parity pins (tests, CPU only): top-K against a full library sort and exhaustive
+ * tie patterns; softmax rows sum to one, shift invariance, E=2 logistic; dispatch
+ * bijection and ordering; E=1 reduces to two library matmuls; k=E equals the
+ * dense gate-weighted sum; identical experts; the truth table of Algorithm 4;
+ * fraction 1 = synchronous layer, fraction 0 = cache; the gradient of Equation 1
+ * by finite differences.
+ * PARITY UNPINNED: the choice of the per-token importance score for the
+ * FRACTION_TOKEN policy (the paper has no fraction form); it is pinned only by
+ * its reduction to Algorithm 4 (FRACTION_PAIR form) and the fraction 0/1 cases.
+ *
+ * Storage: raw inputs (x, weights, biases) arrive as float because every value of
+ * a bf16 or fp32 workload is exactly representable in it; every operation is
+ * carried out in double and every computed array is double.
+ *
+ * Weight layout (rows are output features, as in a linear layer's weight):
+ *   Wg[E][d], W1[E][F][d], b1[E][F], W2[E][d][F], b2[E][d].
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_REFRESH_ALL = 0, ORACLE_REFRESH_ALG4 = 1, ORACLE_REFRESH_FRACTION_TOKEN = 2,
+       ORACLE_REFRESH_FRACTION_PAIR = 3, ORACLE_REFRESH_NONE = 4 };
+
+/* ---- router: logits z[i,e] = sum_c x[i,c] Wg[e,c] + bg[e]  (Algorithm 1, router) ---- */
+void oracle_router_logits(const float* x, const float* Wg, const float* bg,
+                          int T, int d, int E, double* z)
+{
+    for (int i = 0; i < T; ++i)
+        for (int e = 0; e < E; ++e) {
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c)
+                acc += (double)x[(size_t)i * d + c] * (double)Wg[(size_t)e * d + c];
+            if (bg) acc += (double)bg[e];
+            z[(size_t)i * E + e] = acc;
+        }
+}
+
+/* ---- top-K by brute force: sort every token's experts by (logit descending, expert id
+ *      ascending) and keep the first k.  idx[i,j] is the expert of rank j. ---- */
+void oracle_topk(const double* z, int T, int E, int k, int32_t* idx)
+{
+    int* order = (int*)malloc(sizeof(int) * (size_t)E);
+    for (int i = 0; i < T; ++i) {
+        const double* zi = z + (size_t)i * E;
+        for (int e = 0; e < E; ++e) order[e] = e;
+        /* insertion sort: stable, and the starting order is ascending expert id, so equal
+           logits keep the lower id first */
+        for (int a = 1; a < E; ++a) {
+            int ea = order[a];
+            int b = a - 1;
+            while (b >= 0 && zi[order[b]] < zi[ea]) { order[b + 1] = order[b]; --b; }
+            order[b + 1] = ea;
+        }
+        for (int j = 0; j < k; ++j) idx[(size_t)i * k + j] = order[j];
+    }
+    free(order);
+}
+
+/* ---- scores: p = softmax(z) over all E; s[i,j] = p[i, idx[i,j]]; optional renormalisation
+ *      over the k selected ("router scores s_i^e", Section 4.3) ---- */
+void oracle_scores(const double* z, const int32_t* idx, int T, int E, int k, int renorm_topk,
+                   double* p /* [T,E], may be NULL */, double* s /* [T,k] */)
+{
+    double* row = (double*)malloc(sizeof(double) * (size_t)E);
+    for (int i = 0; i < T; ++i) {
+        const double* zi = z + (size_t)i * E;
+        double m = zi[0];
+        for (int e = 1; e < E; ++e) if (zi[e] > m) m = zi[e];
+        double sum = 0.0;
+        for (int e = 0; e < E; ++e) { row[e] = exp(zi[e] - m); sum += row[e]; }
+        for (int e = 0; e < E; ++e) row[e] /= sum;
+        if (p) memcpy(p + (size_t)i * E, row, sizeof(double) * (size_t)E);
+        double ssum = 0.0;
+        for (int j = 0; j < k; ++j) { s[(size_t)i * k + j] = row[idx[(size_t)i * k + j]]; ssum += s[(size_t)i * k + j]; }
+        if (renorm_topk)
+            for (int j = 0; j < k; ++j) s[(size_t)i * k + j] /= ssum;
+    }
+    free(row);
+}
+
+/* ---- refresh mask (Algorithm 4 and its fraction forms) ----
+ * A pair is (token i, slot j); slot 0 is the token's top-1 expert.
+ *   ALL / NONE     : every pair / no pair.
+ *   ALG4(t, n)     : pair is transmitted if j == 0, or if t mod n == 0.
+ *   FRACTION_TOKEN : tokens ordered by (s[i,0] descending, i ascending); the first n_units
+ *                    tokens have all their pairs refreshed.
+ *   FRACTION_PAIR  : pairs ordered by (slot ascending, score descending, token ascending);
+ *                    the first n_units pairs are refreshed.
+ * Returns the number of refreshed pairs, or -1 for an invalid policy. */
+typedef struct { double key; int32_t slot; int32_t token; } rank_item;
+
+static int cmp_rank_item(const void* a, const void* b)
+{
+    const rank_item* p = (const rank_item*)a;
+    const rank_item* q = (const rank_item*)b;
+    if (p->slot != q->slot) return p->slot < q->slot ? -1 : 1;
+    if (p->key != q->key) return p->key > q->key ? -1 : 1;
+    if (p->token != q->token) return p->token < q->token ? -1 : 1;
+    return 0;
+}
+
+int oracle_refresh_mask(const double* s, int T, int k, int policy, int step_t, int stride_n,
+                        int n_units, uint8_t* mask)
+{
+    const size_t N = (size_t)T * k;
+    int R = 0;
+    switch (policy) {
+    case ORACLE_REFRESH_ALL:
+        memset(mask, 1, N);
+        return (int)N;
+    case ORACLE_REFRESH_NONE:
+        memset(mask, 0, N);
+        return 0;
+    case ORACLE_REFRESH_ALG4:
+        if (stride_n < 1 || step_t < 0) return -1;
+        for (int i = 0; i < T; ++i)
+            for (int j = 0; j < k; ++j) {
+                int transmit;
+                if (j == 0) transmit = 1;                       /* top-1 expert: always fresh */
+                else if (step_t % stride_n != 0) transmit = 0;  /* reuse the stale activation */
+                else transmit = 1;                              /* periodic update */
+                mask[(size_t)i * k + j] = (uint8_t)transmit;
+                R += transmit;
+            }
+        return R;
+    case ORACLE_REFRESH_FRACTION_TOKEN: {
+        if (n_units < 0 || n_units > T) return -1;
+        rank_item* it = (rank_item*)malloc(sizeof(rank_item) * (size_t)(T > 0 ? T : 1));
+        for (int i = 0; i < T; ++i) { it[i].key = s[(size_t)i * k]; it[i].slot = 0; it[i].token = i; }
+        qsort(it, (size_t)T, sizeof(rank_item), cmp_rank_item);
+        memset(mask, 0, N);
+        for (int r = 0; r < n_units; ++r)
+            for (int j = 0; j < k; ++j) mask[(size_t)it[r].token * k + j] = 1;
+        free(it);
+        return n_units * k;
+    }
+    case ORACLE_REFRESH_FRACTION_PAIR: {
+        if (n_units < 0 || (size_t)n_units > N) return -1;
+        rank_item* it = (rank_item*)malloc(sizeof(rank_item) * (N > 0 ? N : 1));
+        for (int i = 0; i < T; ++i)
+            for (int j = 0; j < k; ++j) {
+                size_t p = (size_t)i * k + j;
+                it[p].key = s[p]; it[p].slot = j; it[p].token = i;
+            }
+        qsort(it, N, sizeof(rank_item), cmp_rank_item);
+        memset(mask, 0, N);
+        for (int r = 0; r < n_units; ++r) mask[(size_t)it[r].token * k + it[r].slot] = 1;
+        free(it);
+        return n_units;
+    }
+    default:
+        return -1;
+    }
+}
+
+/* ---- dispatch: group the refreshed pairs by expert (Algorithm 1, dispatch) ----
+ * counts[e] = number of refreshed pairs routed to e; offsets = exclusive prefix sum
+ * (E+1 entries); packed rows are ordered by (expert ascending, flat pair id ascending);
+ * perm[r] = flat pair id (i*k + j) held by packed row r; inv[p] = packed row of pair p,
+ * or -1 when the pair is not refreshed.  mask may be NULL (all pairs).  Returns R. */
+int oracle_dispatch(const int32_t* idx, const uint8_t* mask, int T, int k, int E,
+                    int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv)
+{
+    const size_t N = (size_t)T * k;
+    for (int e = 0; e < E; ++e) counts[e] = 0;
+    for (size_t p = 0; p < N; ++p)
+        if (!mask || mask[p]) counts[idx[p]] += 1;
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + counts[e];
+    int r = 0;
+    for (int e = 0; e < E; ++e)
+        for (size_t p = 0; p < N; ++p)
+            if ((!mask || mask[p]) && idx[p] == e) { perm[r] = (int32_t)p; ++r; }
+    for (size_t p = 0; p < N; ++p) inv[p] = -1;
+    for (int q = 0; q < r; ++q) inv[perm[q]] = q;
+    return r;
+}
+
+/* packed row r is a copy of the row of token perm[r] / k */
+void oracle_pack_rows(const float* x, const int32_t* perm, int R, int k, int d, float* x_packed)
+{
+    for (int r = 0; r < R; ++r)
+        memcpy(x_packed + (size_t)r * d, x + (size_t)(perm[r] / k) * d, sizeof(float) * (size_t)d);
+}
+
+/* ---- one expert applied to one row: h = W2 . gelu(W1 . x + b1) + b2,
+ *      gelu(u) = u/2 (1 + erf(u / sqrt 2)) ---- */
+static void expert_row(const float* xrow, const float* W1e, const float* b1e, const float* W2e,
+                       const float* b2e, int d, int F, double* hidden, double* hrow)
+{
+    for (int f = 0; f < F; ++f) {
+        double u = b1e ? (double)b1e[f] : 0.0;
+        const float* w = W1e + (size_t)f * d;
+        for (int c = 0; c < d; ++c) u += (double)xrow[c] * (double)w[c];
+        hidden[f] = 0.5 * u * (1.0 + erf(u / sqrt(2.0)));
+    }
+    for (int c = 0; c < d; ++c) {
+        double acc = b2e ? (double)b2e[c] : 0.0;
+        const float* w = W2e + (size_t)c * F;
+        for (int f = 0; f < F; ++f) acc += hidden[f] * (double)w[f];
+        hrow[c] = acc;
+    }
+}
+
+/* ---- grouped expert FFN over a segment table (Algorithm 1, expert) ----
+ * Rows seg_offsets[g] .. seg_offsets[g+1]-1 of x_packed go through expert seg_expert[g].
+ * With n_seg = E and seg_expert = identity this is the per-expert grouping of dispatch; with
+ * n_seg = W*E_loc it is an expert-parallel receive buffer ordered [source rank][local expert].
+ * rows_sel (optional, n_sel entries): compute only those packed rows, writing h_out[q] for
+ * rows_sel[q]; otherwise every row r is written to h_out[r]. */
+void oracle_expert_ffn(const float* x_packed, const int32_t* seg_offsets, const int32_t* seg_expert,
+                       int n_seg, const float* W1, const float* b1, const float* W2, const float* b2,
+                       int d, int F, const int32_t* rows_sel, int n_sel, double* h_out)
+{
+    const int total = seg_offsets[n_seg];
+    const int n = rows_sel ? n_sel : total;
+#pragma omp parallel
+    {
+        double* hidden = (double*)malloc(sizeof(double) * (size_t)F);
+#pragma omp for schedule(dynamic, 1)
+        for (int q = 0; q < n; ++q) {
+            const int r = rows_sel ? rows_sel[q] : q;
+            int g = 0;
+            while (g < n_seg && !(seg_offsets[g] <= r && r < seg_offsets[g + 1])) ++g;
+            if (g == n_seg) continue; /* row outside every segment: left untouched */
+            const int e = seg_expert[g];
+            expert_row(x_packed + (size_t)r * d,
+                       W1 + (size_t)e * F * d, b1 ? b1 + (size_t)e * F : NULL,
+                       W2 + (size_t)e * d * F, b2 ? b2 + (size_t)e * d : NULL,
+                       d, F, hidden, h_out + (size_t)q * d);
+        }
+        free(hidden);
+    }
+}
+
+/* ---- combine + scale + cache (Algorithm 1 combine/scale; Algorithm 4 reuse) ----
+ * y_i = sum_{j=0}^{k-1} s*_ij h*_ij in slot order.  A refreshed pair takes the fresh packed
+ * row and this step's score and writes both through to the cache; a reused pair takes the
+ * cached row and, unless use_fresh_scores, the cached score.  mask NULL = all refreshed.
+ * tokens_sel (optional): compute only those tokens into y[q]; the cache write-through still
+ * covers only the selected tokens in that case.  Returns 0, or -1 if a reused pair is met
+ * with no cache. */
+int oracle_combine(const double* h_packed, const int32_t* inv, const double* s, const uint8_t* mask,
+                   int T, int k, int d, double* H_cache, double* S_cache, int use_fresh_scores,
+                   const int32_t* tokens_sel, int n_sel, double* y)
+{
+    const int n = tokens_sel ? n_sel : T;
+    for (int q = 0; q < n; ++q) {
+        const int i = tokens_sel ? tokens_sel[q] : q;
+        double* yi = y + (size_t)q * d;
+        for (int c = 0; c < d; ++c) yi[c] = 0.0;
+        for (int j = 0; j < k; ++j) {
+            const size_t p = (size_t)i * k + j;
+            const double* hh;
+            double ss;
+            if (!mask || mask[p]) {
+                hh = h_packed + (size_t)inv[p] * d;
+                ss = s[p];
+                if (H_cache) memcpy(H_cache + p * d, hh, sizeof(double) * (size_t)d);
+                if (S_cache) S_cache[p] = ss;
+            } else {
+                if (!H_cache || !S_cache) return -1;
+                hh = H_cache + p * d;
+                ss = use_fresh_scores ? s[p] : S_cache[p];
+            }
+            for (int c = 0; c < d; ++c) yi[c] += ss * hh[c];
+        }
+    }
+    return 0;
+}
+
+/* ---- expert-parallel receive layout: segment table from recv_counts[W][E_loc] ----
+ * The receive buffer of one shard is ordered [source rank][local expert]; segment
+ * g = src*E_loc + e_loc holds recv_counts[src][e_loc] rows and runs on local expert e_loc. */
+void oracle_ep_segments(const int32_t* recv_counts, int W, int E_loc,
+                        int32_t* seg_offsets, int32_t* seg_expert)
+{
+    seg_offsets[0] = 0;
+    for (int src = 0; src < W; ++src)
+        for (int el = 0; el < E_loc; ++el) {
+            const int g = src * E_loc + el;
+            seg_offsets[g + 1] = seg_offsets[g] + recv_counts[g];
+            seg_expert[g] = el;
+        }
+}
