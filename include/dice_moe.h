@@ -1,0 +1,180 @@
+/*
+ * dice_moe.h -- C-ABI of the MI355X (gfx950) MoE expert layer with DICE's token-level
+ * Conditional Communication.
+ *
+ * The calls follow the paper's statement of one MoE layer under expert parallelism
+ * (supplement, Algorithm 1):
+ *     [s, idx] <- router(x)            moe_gate
+ *     x_d <- all2all_dispatch(x, idx)  moe_dispatch      (one device: group rows by expert)
+ *     x_e <- expert(x_d)               moe_expert_ffn
+ *     x_c <- all2all_combine(x_e)      moe_combine       (one device: back to token order)
+ *     x   <- scale(x_c, s)             moe_combine       (y_i = sum_e s_i^e h_i^e, Section 4.3)
+ * and the per-pair transmit/reuse decision of Conditional Communication (supplement,
+ * Algorithm 4) sits between router and dispatch:      moe_conditional_refresh.
+ *
+ * Conventions for every entry point
+ *   - Returns MOE_OK (0) or a negative moe_status.  Never throws, aborts, allocates device
+ *     memory or synchronises the host.  All work is enqueued on `stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream) of the current device.
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned, row-major
+ *     and contiguous.  moe_shape / moe_policy pointers are HOST pointers read during the call.
+ *   - Errors that the host can see (null pointer, bad shape, bad policy, cold cache) return
+ *     before anything is launched; a failed launch returns MOE_ERR_HIP.  The text of the last
+ *     error of a context is available from moe_last_error().
+ *   - Data-dependent sizes (per-expert counts, number of refreshed pairs) stay on the device;
+ *     buffers are sized for the worst case N = T*k rows.
+ *   - Notation: T tokens, d hidden size, F expert width, E experts, k experts per token,
+ *     pair p = i*k + j = (token i, slot j); slot 0 is the token's top-1 expert.
+ *   - Storage type `dtype` applies to x, Wg, W1, W2, x_packed, h_packed, H_cache and y.
+ *     Scores, probabilities, logits and biases are always float; indices are int32.
+ *   - Weights are stored like a linear layer's weight, rows = output features:
+ *       Wg[E][d],  W1[E][F][d],  b1[E][F],  W2[E][d][F],  b2[E][d].
+ *   - Limits: 1 <= k <= E <= 64; d % 16 == 0 and F % 16 == 0; for MOE_BF16 also d % 64 == 0 and
+ *     F % 64 == 0 (MFMA tile depth); T*k < 2^31 / max(d, F).
+ */
+#ifndef DICE_MOE_H
+#define DICE_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_NULL = -1,       /* a required pointer is NULL */
+    MOE_ERR_SHAPE = -2,      /* a size is out of range or violates a limit above */
+    MOE_ERR_DTYPE = -3,      /* unknown storage type */
+    MOE_ERR_POLICY = -4,     /* refresh policy fields out of range */
+    MOE_ERR_WORKSPACE = -5,  /* workspace pointer missing */
+    MOE_ERR_CACHE_COLD = -6, /* a partial refresh was asked for but no cache was given */
+    MOE_ERR_HIP = -7         /* the HIP runtime refused a launch */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+typedef struct {
+    int32_t T_max;       /* largest token count of any call; packed buffers hold T_max*k rows */
+    int32_t d, F, E, k;
+    int32_t dtype;       /* moe_dtype */
+    int32_t renorm_topk; /* 0: scores are the softmax over all E experts taken at the selected
+                            ones (default; the paper only says "router scores");
+                            1: additionally divided by their sum over the k selected */
+} moe_shape;
+
+/* Which (token, slot) pairs are recomputed ("transmitted") in this step; the others reuse the
+ * cached expert output of an earlier step (Algorithm 4). */
+typedef enum {
+    MOE_REFRESH_ALL = 0,            /* synchronous layer: every pair */
+    MOE_REFRESH_ALG4 = 1,           /* Algorithm 4: slot 0 always; other slots iff step_t % stride_n == 0 */
+    MOE_REFRESH_FRACTION_TOKEN = 2, /* the n_units tokens with the largest top-1 score, all their slots */
+    MOE_REFRESH_FRACTION_PAIR = 3,  /* the first n_units pairs in the order (slot asc, score desc, token asc) */
+    MOE_REFRESH_NONE = 4            /* no pair: the output is rebuilt from the cache */
+} moe_policy_kind;
+
+typedef struct {
+    int32_t kind;             /* moe_policy_kind */
+    int32_t step_t, stride_n; /* ALG4: step_t >= 0, stride_n >= 1 */
+    int32_t n_units;          /* FRACTION_TOKEN: 0..T tokens; FRACTION_PAIR: 0..T*k pairs.  The
+                                 caller rounds a fraction to this integer. */
+    int32_t use_fresh_scores; /* which score scales a reused cached output (supplement, "Expert
+                                 Score Scaling"): 0 = the cached score that belonged to the stale
+                                 input (the paper's choice), 1 = this step's score */
+} moe_policy;
+
+typedef struct moe_ctx moe_ctx; /* opaque; host memory only (shape, last error) */
+
+/* Create / destroy a context.  `shape` is validated here (MOE_ERR_SHAPE / MOE_ERR_DTYPE). */
+int moe_create(moe_ctx** out, const moe_shape* shape);
+int moe_destroy(moe_ctx* ctx);
+
+/* Bytes of device workspace that moe_conditional_refresh, moe_dispatch and moe_expert_ffn may
+ * use for T_max tokens (the FFN's hidden activations [T_max*k, F] dominate).  One workspace can
+ * serve all three calls of a layer, and all layers, on one stream. */
+size_t moe_workspace_bytes(const moe_ctx* ctx);
+
+/* Text of the last error recorded on this context ("" if none); valid until the next call. */
+const char* moe_last_error(const moe_ctx* ctx);
+/* Name of a status code. */
+const char* moe_status_string(int status);
+
+/* Router (Algorithm 1, "[s, idx] <- router(x)"; K activated experts per token, Conditional
+ * Communication figure).  logits z = x . Wg^T (+ bg), accumulated in float; expert_idx[i][j] is
+ * the expert with the j-th largest logit of token i, equal logits going to the lower expert id;
+ * scores[i][j] = softmax_over_E(z_i)[expert_idx[i][j]] (renormalised over the k if the shape
+ * says so).
+ *   in : x[T][d], Wg[E][d] (dtype), bg[E] float or NULL
+ *   out: scores[T][k] float, expert_idx[T][k] int32,
+ *        probs_all[T][E] float or NULL, logits[T][E] float or NULL
+ * T may be 0 (nothing is launched). */
+int moe_gate(moe_ctx* ctx, const void* x, const void* Wg, const float* bg, int32_t T,
+             float* scores, int32_t* expert_idx, float* probs_all, float* logits, void* stream);
+
+/* Conditional Communication decision (Algorithm 4 and its fraction forms, see moe_policy_kind).
+ * Ordering is exact on the float bit patterns of `scores`; equal scores go to the lower token.
+ *   in : scores[T][k], expert_idx[T][k] (unused by the current policies, may be NULL)
+ *   out: mask[T][k] uint8 (1 = refresh), n_refresh[1] int32 on the device
+ * workspace: moe_workspace_bytes(); used by the FRACTION policies only. */
+int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* expert_idx,
+                            int32_t T, const moe_policy* policy, uint8_t* mask,
+                            int32_t* n_refresh, void* workspace, void* stream);
+
+/* Dispatch on one device (Algorithm 1, dispatch): a stable counting sort of the refreshed pairs
+ * by expert id and a row gather into an expert-contiguous buffer.  With experts partitioned in
+ * blocks over expert-parallel ranks the same order is (destination rank, local expert, token),
+ * i.e. `counts` viewed as [W][E/W] are the all-to-all send counts and x_packed is the send buffer.
+ *   in : x[T][d], expert_idx[T][k], mask[T][k] or NULL (= every pair)
+ *   out: x_packed[R][d] rows of the refreshed pairs ordered by (expert asc, pair id asc), copied
+ *        bit for bit (rows >= R are left untouched); counts[E]; offsets[E+1] exclusive prefix
+ *        sums (offsets[E] = R); perm[T*k]: pair id of packed row r, -1 for r >= R;
+ *        inv[T*k]: packed row of pair p, -1 if p is not refreshed. */
+int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const uint8_t* mask,
+                 int32_t T, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
+                 int32_t* inv, void* workspace, void* stream);
+
+/* Grouped expert FFN (Algorithm 1, "x_e <- expert(x_d)"; experts are feed-forward networks):
+ * for every segment g, rows seg_offsets[g] .. seg_offsets[g+1]-1 of x_packed go through expert
+ * seg_expert[g]:  h = W2_e . gelu(W1_e . x + b1_e) + b2_e,  gelu(u) = u/2 (1 + erf(u/sqrt 2)).
+ * MOE_BF16: bf16 MFMA with float accumulation, the hidden activation is rounded to bf16 once.
+ * Segments generalise the per-expert grouping of moe_dispatch (n_segments = E, seg_offsets =
+ * offsets, seg_expert = 0..E-1) to an expert-parallel receive buffer ordered
+ * [source rank][local expert] (n_segments = W * E_loc, see moe_ep_segments).
+ *   in : x_packed[>= seg_offsets[n_segments]][d]; seg_offsets[n_segments+1], seg_expert[n_segments]
+ *        (device); max_rows >= seg_offsets[n_segments] (host bound that sizes the launch,
+ *        max_rows <= T_max*k); W1, W2 (dtype); b1, b2 float or NULL; every seg_expert < E
+ *   out: h_packed[..][d] (dtype); rows outside every segment are left untouched
+ * workspace: moe_workspace_bytes(). 1 <= n_segments <= 1024. */
+int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* seg_offsets,
+                   const int32_t* seg_expert, int32_t n_segments, int32_t max_rows,
+                   const void* W1, const float* b1, const void* W2, const float* b2,
+                   void* h_packed, void* workspace, void* stream);
+
+/* Combine + scale + cache blend (Algorithm 1 combine/scale; Algorithm 4 "reuse stale h"):
+ *   y_i = sum_{j=0..k-1} s*_ij h*_ij   accumulated in float in slot order,
+ * where a refreshed pair takes h_packed[inv[p]] and scores[p] and writes both through to
+ * H_cache[p] / S_cache[p] (when caches are given), and a reused pair takes H_cache[p] and
+ * S_cache[p] (or scores[p] if use_fresh_scores).  The cache is keyed by (token, slot): a change of
+ * expert_idx[i][j] on a reused pair is not detected, as with a persistent combine buffer.
+ *   in : h_packed[R][d], inv[T*k], scores[T][k], mask[T][k] or NULL (= every pair refreshed)
+ *   io : H_cache[T][k][d] (dtype) and S_cache[T][k] float, or both NULL when mask is NULL
+ *   out: y[T][d] (dtype)
+ * A non-NULL mask with a NULL cache returns MOE_ERR_CACHE_COLD; whether a given cache has been
+ * filled by an earlier full refresh is the caller's responsibility. */
+int moe_combine(moe_ctx* ctx, const void* h_packed, const int32_t* inv, const float* scores,
+                const uint8_t* mask, int32_t T, void* H_cache, float* S_cache,
+                int32_t use_fresh_scores, void* y, void* stream);
+
+/* Segment table of an expert-parallel receive buffer (expert-parallelism figure: each device
+ * holds a subset of the experts and receives the rows routed to them from every rank).
+ * The buffer is ordered [source rank][local expert]; segment g = src*E_loc + e_loc has
+ * recv_counts[g] rows and runs on local expert e_loc.
+ *   in : recv_counts[W*E_loc] (device)      out: seg_offsets[W*E_loc+1], seg_expert[W*E_loc] */
+int moe_ep_segments(moe_ctx* ctx, const int32_t* recv_counts, int32_t W, int32_t E_loc,
+                    int32_t* seg_offsets, int32_t* seg_expert, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DICE_MOE_H */

@@ -44,6 +44,7 @@
  *   Wg[E][d], W1[E][F][d], b1[E][F], W2[E][d][F], b2[E][d].
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -313,3 +314,6 @@ void oracle_ep_segments(const int32_t* recv_counts, int W, int E_loc,
             seg_expert[g] = el;
         }
 }
+
+/* threads the row-parallel expert loop will use (reported beside the oracle's timings) */
+int oracle_num_threads(void) { return omp_get_max_threads(); }

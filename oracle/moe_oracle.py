@@ -176,6 +176,10 @@ def combine(h_packed, inv, s, mask, H_cache=None, S_cache=None, use_fresh_scores
     return y
 
 
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
 def ep_segments(recv_counts):
     """Segment table of an expert-parallel receive buffer ordered [source rank][local expert]."""
     rc = _i32(recv_counts)

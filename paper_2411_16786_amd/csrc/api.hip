@@ -1,0 +1,231 @@
+// C-ABI of the library: argument validation on the host, then the kernel launchers.
+// See include/dice_moe.h for the meaning of every argument.
+#include "../../include/dice_moe.h"
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "kernels.hpp"
+
+struct moe_ctx {
+    moe_shape shape;
+    char err[256];
+};
+
+namespace {
+
+using namespace dicemoe;
+
+int fail(moe_ctx* ctx, int status, const char* fmt, long a = 0, long b = 0)
+{
+    if (ctx) std::snprintf(ctx->err, sizeof(ctx->err), fmt, a, b);
+    return status;
+}
+
+int hip_result(moe_ctx* ctx, hipError_t err, const char* what)
+{
+    if (err == hipSuccess) return MOE_OK;
+    if (ctx) std::snprintf(ctx->err, sizeof(ctx->err), "%s: %s", what, hipGetErrorString(err));
+    return MOE_ERR_HIP;
+}
+
+bool is_bf16(const moe_ctx* ctx) { return ctx->shape.dtype == MOE_BF16; }
+size_t elem_bytes(const moe_ctx* ctx) { return is_bf16(ctx) ? 2 : 4; }
+
+int check_T(moe_ctx* ctx, int32_t T)
+{
+    if (T < 0 || T > ctx->shape.T_max) return fail(ctx, MOE_ERR_SHAPE, "T=%ld outside 0..T_max=%ld", T, ctx->shape.T_max);
+    return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moe_create(moe_ctx** out, const moe_shape* s)
+{
+    if (!out || !s) return MOE_ERR_NULL;
+    *out = nullptr;
+    if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_DTYPE;
+    if (s->T_max < 0 || s->d < 1 || s->F < 1 || s->E < 1 || s->k < 1) return MOE_ERR_SHAPE;
+    if (s->k > s->E || s->E > 64) return MOE_ERR_SHAPE;
+    const int mult = (s->dtype == MOE_BF16) ? 64 : 16;
+    if (s->d % mult != 0 || s->F % mult != 0) return MOE_ERR_SHAPE;
+    const long long rows = static_cast<long long>(s->T_max) * s->k;
+    const long long widest = s->d > s->F ? s->d : s->F;
+    if (rows * widest >= (1ll << 31)) return MOE_ERR_SHAPE;
+    if (static_cast<long long>(s->T_max) * s->E >= (1ll << 31)) return MOE_ERR_SHAPE;
+    moe_ctx* ctx = new (std::nothrow) moe_ctx;
+    if (!ctx) return MOE_ERR_NULL;
+    ctx->shape = *s;
+    ctx->shape.renorm_topk = s->renorm_topk ? 1 : 0;
+    ctx->err[0] = '\0';
+    *out = ctx;
+    return MOE_OK;
+}
+
+int moe_destroy(moe_ctx* ctx)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    delete ctx;
+    return MOE_OK;
+}
+
+size_t moe_workspace_bytes(const moe_ctx* ctx)
+{
+    if (!ctx) return 0;
+    const size_t rows = static_cast<size_t>(ctx->shape.T_max) * ctx->shape.k;
+    const size_t hidden = rows * ctx->shape.F * (ctx->shape.dtype == MOE_BF16 ? 2 : 4);
+    return ((hidden + 255) / 256) * 256 + 4096;
+}
+
+const char* moe_last_error(const moe_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+const char* moe_status_string(int status)
+{
+    switch (status) {
+    case MOE_OK: return "MOE_OK";
+    case MOE_ERR_NULL: return "MOE_ERR_NULL";
+    case MOE_ERR_SHAPE: return "MOE_ERR_SHAPE";
+    case MOE_ERR_DTYPE: return "MOE_ERR_DTYPE";
+    case MOE_ERR_POLICY: return "MOE_ERR_POLICY";
+    case MOE_ERR_WORKSPACE: return "MOE_ERR_WORKSPACE";
+    case MOE_ERR_CACHE_COLD: return "MOE_ERR_CACHE_COLD";
+    case MOE_ERR_HIP: return "MOE_ERR_HIP";
+    default: return "MOE_ERR_UNKNOWN";
+    }
+}
+
+int moe_gate(moe_ctx* ctx, const void* x, const void* Wg, const float* bg, int32_t T, float* scores,
+             int32_t* expert_idx, float* probs_all, float* logits, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (int rc = check_T(ctx, T)) return rc;
+    if (!x || !Wg || !scores || !expert_idx) return fail(ctx, MOE_ERR_NULL, "moe_gate: null pointer");
+    if (T == 0) return MOE_OK;
+    const moe_shape& s = ctx->shape;
+    return hip_result(ctx,
+                      launch_gate(is_bf16(ctx), x, Wg, bg, T, s.d, s.E, s.k, s.renorm_topk, scores, expert_idx,
+                                  probs_all, logits, static_cast<hipStream_t>(stream)),
+                      "moe_gate");
+}
+
+int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* expert_idx, int32_t T,
+                            const moe_policy* policy, uint8_t* mask, int32_t* n_refresh, void* workspace,
+                            void* stream)
+{
+    (void)expert_idx;
+    (void)workspace;
+    if (!ctx) return MOE_ERR_NULL;
+    if (int rc = check_T(ctx, T)) return rc;
+    if (!policy || !mask || !n_refresh) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: null pointer");
+    const moe_shape& s = ctx->shape;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const long N = static_cast<long>(T) * s.k;
+    switch (policy->kind) {
+    case MOE_REFRESH_ALL:
+    case MOE_REFRESH_NONE:
+        return hip_result(ctx, launch_refresh_simple(policy->kind, T, s.k, 0, 1, mask, n_refresh, st),
+                          "moe_conditional_refresh");
+    case MOE_REFRESH_ALG4:
+        if (policy->stride_n < 1 || policy->step_t < 0)
+            return fail(ctx, MOE_ERR_POLICY, "ALG4 needs step_t >= 0 and stride_n >= 1 (got %ld, %ld)",
+                        policy->step_t, policy->stride_n);
+        return hip_result(ctx,
+                          launch_refresh_simple(MOE_REFRESH_ALG4, T, s.k, policy->step_t, policy->stride_n, mask,
+                                                n_refresh, st),
+                          "moe_conditional_refresh");
+    case MOE_REFRESH_FRACTION_TOKEN:
+        if (policy->n_units < 0 || policy->n_units > T)
+            return fail(ctx, MOE_ERR_POLICY, "FRACTION_TOKEN n_units=%ld outside 0..T=%ld", policy->n_units, T);
+        if (!scores) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: scores is null");
+        return hip_result(ctx,
+                          launch_refresh_select(scores, T, s.k, 0, policy->n_units, true, policy->n_units * s.k,
+                                                mask, n_refresh, st),
+                          "moe_conditional_refresh");
+    case MOE_REFRESH_FRACTION_PAIR: {
+        if (policy->n_units < 0 || policy->n_units > N)
+            return fail(ctx, MOE_ERR_POLICY, "FRACTION_PAIR n_units=%ld outside 0..T*k=%ld", policy->n_units, N);
+        if (!scores) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: scores is null");
+        if (policy->n_units == N)
+            return hip_result(ctx, launch_refresh_simple(MOE_REFRESH_ALL, T, s.k, 0, 1, mask, n_refresh, st),
+                              "moe_conditional_refresh");
+        // slots before `slot` are refreshed for every token, slot `slot` for its m best tokens
+        const int slot = T > 0 ? policy->n_units / T : 0;
+        const int m = T > 0 ? policy->n_units % T : 0;
+        return hip_result(ctx,
+                          launch_refresh_select(scores, T, s.k, slot, m, false, policy->n_units, mask, n_refresh, st),
+                          "moe_conditional_refresh");
+    }
+    default:
+        return fail(ctx, MOE_ERR_POLICY, "unknown policy kind %ld", policy->kind);
+    }
+}
+
+int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const uint8_t* mask, int32_t T,
+                 void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv, void* workspace,
+                 void* stream)
+{
+    (void)workspace;
+    if (!ctx) return MOE_ERR_NULL;
+    if (int rc = check_T(ctx, T)) return rc;
+    if (!x || !expert_idx || !x_packed || !counts || !offsets || !perm || !inv)
+        return fail(ctx, MOE_ERR_NULL, "moe_dispatch: null pointer");
+    const moe_shape& s = ctx->shape;
+    return hip_result(ctx,
+                      launch_dispatch(is_bf16(ctx), x, expert_idx, mask, T, s.d, s.E, s.k, x_packed, counts, offsets,
+                                      perm, inv, static_cast<hipStream_t>(stream)),
+                      "moe_dispatch");
+}
+
+int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* seg_offsets, const int32_t* seg_expert,
+                   int32_t n_segments, int32_t max_rows, const void* W1, const float* b1, const void* W2,
+                   const float* b2, void* h_packed, void* workspace, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    const moe_shape& s = ctx->shape;
+    if (n_segments < 1 || n_segments > 1024)
+        return fail(ctx, MOE_ERR_SHAPE, "n_segments=%ld outside 1..1024", n_segments);
+    if (max_rows < 0 || static_cast<long long>(max_rows) > static_cast<long long>(s.T_max) * s.k)
+        return fail(ctx, MOE_ERR_SHAPE, "max_rows=%ld outside 0..T_max*k=%ld", max_rows, static_cast<long>(s.T_max) * s.k);
+    if (!x_packed || !seg_offsets || !seg_expert || !W1 || !W2 || !h_packed)
+        return fail(ctx, MOE_ERR_NULL, "moe_expert_ffn: null pointer");
+    if (!workspace) return fail(ctx, MOE_ERR_WORKSPACE, "moe_expert_ffn: workspace is null");
+    return hip_result(ctx,
+                      launch_expert_ffn(is_bf16(ctx), x_packed, seg_offsets, seg_expert, n_segments, max_rows, s.d,
+                                        s.F, W1, b1, W2, b2, h_packed, workspace, static_cast<hipStream_t>(stream)),
+                      "moe_expert_ffn");
+}
+
+int moe_combine(moe_ctx* ctx, const void* h_packed, const int32_t* inv, const float* scores, const uint8_t* mask,
+                int32_t T, void* H_cache, float* S_cache, int32_t use_fresh_scores, void* y, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (int rc = check_T(ctx, T)) return rc;
+    if (!h_packed || !inv || !scores || !y) return fail(ctx, MOE_ERR_NULL, "moe_combine: null pointer");
+    if (mask && (!H_cache || !S_cache))
+        return fail(ctx, MOE_ERR_CACHE_COLD, "moe_combine: a refresh mask was given without a cache");
+    if ((H_cache == nullptr) != (S_cache == nullptr))
+        return fail(ctx, MOE_ERR_NULL, "moe_combine: H_cache and S_cache must be given together");
+    const moe_shape& s = ctx->shape;
+    return hip_result(ctx,
+                      launch_combine(is_bf16(ctx), h_packed, inv, scores, mask, T, s.d, s.k, H_cache, S_cache,
+                                     use_fresh_scores ? 1 : 0, y, static_cast<hipStream_t>(stream)),
+                      "moe_combine");
+}
+
+int moe_ep_segments(moe_ctx* ctx, const int32_t* recv_counts, int32_t W, int32_t E_loc, int32_t* seg_offsets,
+                    int32_t* seg_expert, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (W < 1 || E_loc < 1 || static_cast<long long>(W) * E_loc > 1024 || E_loc > ctx->shape.E)
+        return fail(ctx, MOE_ERR_SHAPE, "moe_ep_segments: W=%ld, E_loc=%ld out of range", W, E_loc);
+    if (!recv_counts || !seg_offsets || !seg_expert) return fail(ctx, MOE_ERR_NULL, "moe_ep_segments: null pointer");
+    return hip_result(ctx,
+                      launch_ep_segments(recv_counts, W * E_loc, E_loc, seg_offsets, seg_expert,
+                                         static_cast<hipStream_t>(stream)),
+                      "moe_ep_segments");
+}
+
+}  // extern "C"

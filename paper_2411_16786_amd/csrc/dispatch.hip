@@ -1,0 +1,174 @@
+// Dispatch on one device (Algorithm 1, "x_d <- all2all_dispatch(x, idx)"): group the refreshed
+// (token, slot) pairs by destination expert with a stable counting sort, then gather the token
+// rows into the expert-contiguous buffer.
+//
+// dispatch_index_kernel: one workgroup of 16 wavefronts.  Wave w owns the contiguous range of
+// pair ids [w*L, (w+1)*L), so "wave-major, then lane order" is ascending pair id and the sort is
+// stable by construction.  Lanes that hold the same expert find each other with six ballots (one
+// per bit of the expert id); the lowest such lane keeps a per-wave, per-expert running count in
+// LDS.  Phase A counts, a scan over (expert, wave) turns the counts into bases, phase B walks the
+// range again and writes perm / inv.  All integer work, no atomics: the result is unique.
+//
+// dispatch_gather_kernel: one wavefront per token reads the row once (16 bytes per lane per
+// pass) and stores it to each of its refreshed slots' packed rows; bound by HBM traffic
+// T*d*b read + R*d*b written.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace dicemoe {
+
+constexpr int kIdxThreads = 1024;
+constexpr int kIdxWaves = kIdxThreads / kWave;
+
+// lanes of this wave that are live and hold the same expert id as the calling lane
+__device__ __forceinline__ uint64_t same_expert_peers(bool live, int e) {
+    uint64_t peers = __ballot(live);
+#pragma unroll
+    for (int b = 0; b < 6; ++b) {
+        const bool bit = (e >> b) & 1;
+        const uint64_t bb = __ballot(bit);
+        peers &= bit ? bb : ~bb;
+    }
+    return peers;
+}
+
+__global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32_t* __restrict__ expert_idx,
+                                                                    const uint8_t* __restrict__ mask, int N, int E,
+                                                                    int32_t* __restrict__ counts,
+                                                                    int32_t* __restrict__ offsets,
+                                                                    int32_t* __restrict__ perm,
+                                                                    int32_t* __restrict__ inv)
+{
+    __shared__ volatile int wave_run[kIdxWaves][kMaxExperts];  // counts, then running bases
+    __shared__ int s_cnt[kMaxExperts];
+    __shared__ int s_off[kMaxExperts + 1];
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const int lane = lane_id();
+    const int L = (((N + kIdxWaves - 1) / kIdxWaves) + kWave - 1) / kWave * kWave;
+    const int lo = wave * L;
+    const int hi = (lo + L < N) ? lo + L : N;
+
+    wave_run[tid / kMaxExperts][tid % kMaxExperts] = 0;   // 1024 threads cover the 16 x 64 table
+    __syncthreads();
+
+    // phase A: per-wave, per-expert counts of refreshed pairs
+    for (int p0 = lo; p0 < hi; p0 += kWave) {
+        const int p = p0 + lane;
+        bool live = p < hi && (mask == nullptr || mask[p] != 0);
+        int e = live ? expert_idx[p] : 0;
+        if (static_cast<unsigned>(e) >= static_cast<unsigned>(E)) { live = false; e = 0; }  // ignore a bad id
+        const uint64_t peers = same_expert_peers(live, e);
+        if (live && (peers & lanemask_lt()) == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+
+    // exclusive scan over waves for each expert; then over experts
+    if (tid < E) {
+        int run = 0;
+        for (int w = 0; w < kIdxWaves; ++w) {
+            const int c = wave_run[w][tid];
+            wave_run[w][tid] = run;
+            run += c;
+        }
+        s_cnt[tid] = run;
+        counts[tid] = run;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) { s_off[e] = run; offsets[e] = run; run += s_cnt[e]; }
+        s_off[E] = run;
+        offsets[E] = run;
+    }
+    __syncthreads();
+    const int R = s_off[E];
+
+    // phase B: final positions
+    for (int p0 = lo; p0 < hi; p0 += kWave) {
+        const int p = p0 + lane;
+        const bool in_range = p < hi;
+        bool live = in_range && (mask == nullptr || mask[p] != 0);
+        int e = live ? expert_idx[p] : 0;
+        if (static_cast<unsigned>(e) >= static_cast<unsigned>(E)) { live = false; e = 0; }
+        const uint64_t peers = same_expert_peers(live, e);
+        const int before = __popcll(peers & lanemask_lt());
+        int r = -1;
+        if (live) r = s_off[e] + wave_run[wave][e] + before;
+        __builtin_amdgcn_wave_barrier();
+        if (live && before == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+        if (live) perm[r] = p;
+        if (in_range) inv[p] = r;
+    }
+    for (int r = R + tid; r < N; r += kIdxThreads) perm[r] = -1;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void dispatch_gather_kernel(const T* __restrict__ x, const int32_t* __restrict__ inv,
+                                                              int T_tok, int d, int k, T* __restrict__ x_packed)
+{
+    constexpr int V = Store<T>::kVec;
+    const int tok = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (tok >= T_tok) return;
+    const int lane = lane_id();
+    const int nvec = d / V;
+    const int32_t* rows = inv + static_cast<size_t>(tok) * k;
+    bool any = false;
+    for (int j = 0; j < k; ++j) any |= rows[j] >= 0;
+    if (!any) return;
+    const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(tok) * d);
+    uint4* dst = reinterpret_cast<uint4*>(x_packed);
+    for (int c = lane; c < nvec; c += kWave) {
+        const uint4 v = src[c];
+        for (int j = 0; j < k; ++j) {
+            const int r = rows[j];
+            if (r >= 0) dst[static_cast<size_t>(r) * nvec + c] = v;
+        }
+    }
+}
+
+hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const uint8_t* mask, int T_tok, int d,
+                           int E, int k, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
+                           int32_t* inv, hipStream_t stream)
+{
+    const int N = T_tok * k;
+    hipLaunchKernelGGL(dispatch_index_kernel, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
+                       offsets, perm, inv);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || T_tok == 0) return err;
+    const int blocks = (T_tok + 3) / 4;
+    if (bf16)
+        hipLaunchKernelGGL(dispatch_gather_kernel<bf16_t>, dim3(blocks), dim3(256), 0, stream,
+                           static_cast<const bf16_t*>(x), inv, T_tok, d, k, static_cast<bf16_t*>(x_packed));
+    else
+        hipLaunchKernelGGL(dispatch_gather_kernel<float>, dim3(blocks), dim3(256), 0, stream,
+                           static_cast<const float*>(x), inv, T_tok, d, k, static_cast<float*>(x_packed));
+    return hipGetLastError();
+}
+
+__global__ void ep_segments_kernel(const int32_t* __restrict__ recv_counts, int n_seg, int E_loc,
+                                   int32_t* __restrict__ seg_offsets, int32_t* __restrict__ seg_expert)
+{
+    // tiny table (at most 1024 entries): one thread walks it
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        int run = 0;
+        for (int g = 0; g < n_seg; ++g) {
+            seg_offsets[g] = run;
+            seg_expert[g] = g % E_loc;
+            run += recv_counts[g];
+        }
+        seg_offsets[n_seg] = run;
+    }
+}
+
+hipError_t launch_ep_segments(const int32_t* recv_counts, int n_seg, int E_loc, int32_t* seg_offsets,
+                              int32_t* seg_expert, hipStream_t stream)
+{
+    hipLaunchKernelGGL(ep_segments_kernel, dim3(1), dim3(64), 0, stream, recv_counts, n_seg, E_loc, seg_offsets,
+                       seg_expert);
+    return hipGetLastError();
+}
+
+}  // namespace dicemoe

@@ -1,0 +1,295 @@
+// Grouped expert FFN (Algorithm 1, "x_e <- expert(x_d)"; experts are feed-forward networks):
+// for every segment of packed rows, h = W2_e . gelu(W1_e . x + b1_e) + b2_e with the exact erf
+// GELU.  Two grouped GEMMs with "rows x K" activations and "N x K" weights, both K-contiguous:
+//   GEMM1: hidden[r, f] = gelu(sum_c x[r, c] W1_e[f, c] + b1_e[f])   (rounded to the storage type)
+//   GEMM2: h[r, c]      =       sum_f hidden[r, f] W2_e[c, f] + b2_e[c]
+//
+// Variable-M scheduling: segment sizes live on the device, so the grid is launched for the worst
+// case (ceil(max_rows/BM) + n_segments row tiles) and each workgroup finds its (segment, row tile)
+// by walking the segment table; surplus workgroups exit at once.  Row tiles never straddle two
+// segments, tail rows are clamped on load and masked on store.
+//
+// bf16 path: 256 threads = 4 wavefronts in a 2x2 grid, each wavefront owns a (BM/2)x(BN/2) block
+// of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, float accumulation).  A and B tiles of depth
+// BK = 64 go global -> registers -> LDS with the next tile's global loads in flight during the
+// MFMAs.  LDS rows are 128 bytes; the 16-byte chunk index is XOR-swizzled with row bits so that
+// the fragment reads (32 consecutive rows, same chunk) and the tile stores spread over all banks.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace dicemoe {
+
+typedef __bf16 bf16x8_v __attribute__((ext_vector_type(8)));
+typedef float f32x16_v __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float gelu_erf(float u) {
+    return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
+}
+
+// Walk the segment table: which segment and which rows does row tile `tile` cover?
+__device__ __forceinline__ bool find_row_tile(const int32_t* __restrict__ seg_offsets, int n_seg, int BM, int tile,
+                                              int& seg, int& row0, int& row_end)
+{
+    int begin = seg_offsets[0];
+    for (int g = 0; g < n_seg; ++g) {
+        const int end = seg_offsets[g + 1];
+        const int cnt = end - begin;
+        const int nt = (cnt + BM - 1) / BM;
+        if (tile < nt) {
+            seg = g;
+            row0 = begin + tile * BM;
+            row_end = end;
+            return true;
+        }
+        tile -= nt;
+        begin = end;
+    }
+    return false;
+}
+
+// swizzle of the 16-byte chunk index inside a 128-byte LDS row (8 chunks per row)
+__device__ __forceinline__ int swz8(int row) {
+    return ((row >> 1) & 3) | ((((row) & 1) ^ ((row >> 3) & 1)) << 2);
+}
+
+template <int BM, int BN, bool GELU>
+__global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                            const float* __restrict__ bias, bf16_t* __restrict__ C,
+                                                            int N, int K, const int32_t* __restrict__ seg_offsets,
+                                                            const int32_t* __restrict__ seg_expert, int n_seg,
+                                                            int n_tiles_n)
+{
+    constexpr int BK = 64;
+    constexpr int CH = BK / 8;          // 16-byte chunks per tile row
+    constexpr int WM = BM / 2, WN = BN / 2;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int A_PASSES = BM / 32;   // 256 threads cover 32 rows x 8 chunks per pass
+    constexpr int B_PASSES = BN / 32;
+    __shared__ uint4 As[BM * CH];
+    __shared__ uint4 Bs[BN * CH];
+
+    const int tile_m = blockIdx.x / n_tiles_n;
+    const int tile_n = blockIdx.x % n_tiles_n;
+    int seg, row0, row_end;
+    if (!find_row_tile(seg_offsets, n_seg, BM, tile_m, seg, row0, row_end)) return;
+    const int e = seg_expert[seg];
+    const int n0 = tile_n * BN;
+    const bf16_t* We = W + static_cast<size_t>(e) * N * K;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // global -> register staging: thread covers chunk (tid % 8) of rows (tid / 8) + 32*pass
+    const int ld_chunk = tid & 7;
+    const int ld_row = tid >> 3;
+    const uint4* a_src[A_PASSES];
+    const uint4* b_src[B_PASSES];
+#pragma unroll
+    for (int p = 0; p < A_PASSES; ++p) {
+        int r = row0 + ld_row + 32 * p;
+        if (r >= row_end) r = row_end - 1;                    // clamp: tail rows repeat the last row
+        a_src[p] = reinterpret_cast<const uint4*>(A + static_cast<size_t>(r) * K) + ld_chunk;
+    }
+#pragma unroll
+    for (int p = 0; p < B_PASSES; ++p) {
+        int n = n0 + ld_row + 32 * p;
+        if (n >= N) n = N - 1;
+        b_src[p] = reinterpret_cast<const uint4*>(We + static_cast<size_t>(n) * K) + ld_chunk;
+    }
+    uint4 a_reg[A_PASSES], b_reg[B_PASSES];
+#pragma unroll
+    for (int p = 0; p < A_PASSES; ++p) a_reg[p] = a_src[p][0];
+#pragma unroll
+    for (int p = 0; p < B_PASSES; ++p) b_reg[p] = b_src[p][0];
+
+    f32x16_v acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = K / BK;
+    for (int kt = 0; kt < nk; ++kt) {
+#pragma unroll
+        for (int p = 0; p < A_PASSES; ++p) {
+            const int r = ld_row + 32 * p;
+            As[r * CH + (ld_chunk ^ swz8(r))] = a_reg[p];
+        }
+#pragma unroll
+        for (int p = 0; p < B_PASSES; ++p) {
+            const int r = ld_row + 32 * p;
+            Bs[r * CH + (ld_chunk ^ swz8(r))] = b_reg[p];
+        }
+        __syncthreads();
+        if (kt + 1 < nk) {
+            const int koff = (kt + 1) * CH;
+#pragma unroll
+            for (int p = 0; p < A_PASSES; ++p) a_reg[p] = a_src[p][koff];
+#pragma unroll
+            for (int p = 0; p < B_PASSES; ++p) b_reg[p] = b_src[p][koff];
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int chunk = kk * 2 + (lane >> 5);
+            bf16x8_v af[TM], bfr[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int r = wm * WM + i * 32 + (lane & 31);
+                const uint4 v = As[r * CH + (chunk ^ swz8(r))];
+                af[i] = *reinterpret_cast<const bf16x8_v*>(&v);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int r = wn * WN + j * 32 + (lane & 31);
+                const uint4 v = Bs[r * CH + (chunk ^ swz8(r))];
+                bfr[j] = *reinterpret_cast<const bf16x8_v*>(&v);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: accumulator element v of lane l sits at column (l % 32), row 8*(v/4) + 4*(l/32) + v%4
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + wn * WN + j * 32 + (lane & 31);
+        if (n >= N) continue;
+        const float bv = bias ? bias[static_cast<size_t>(e) * N + n] : 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = row0 + wm * WM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                if (r < row_end) {
+                    float val = acc[i][j][v] + bv;
+                    if (GELU) val = gelu_erf(val);
+                    C[static_cast<size_t>(r) * N + n] = float_to_bf16(val);
+                }
+            }
+        }
+    }
+}
+
+// float path (small workloads): 64x64 tile, depth 16, each thread a 4x4 block, plain FMAs in a
+// fixed order.
+template <bool GELU>
+__global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ W,
+                                                           const float* __restrict__ bias, float* __restrict__ C,
+                                                           int N, int K, const int32_t* __restrict__ seg_offsets,
+                                                           const int32_t* __restrict__ seg_expert, int n_seg,
+                                                           int n_tiles_n)
+{
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float As[BK][BM + 4];
+    __shared__ float Bs[BK][BN + 4];
+    const int tile_m = blockIdx.x / n_tiles_n;
+    const int tile_n = blockIdx.x % n_tiles_n;
+    int seg, row0, row_end;
+    if (!find_row_tile(seg_offsets, n_seg, BM, tile_m, seg, row0, row_end)) return;
+    const int e = seg_expert[seg];
+    const int n0 = tile_n * BN;
+    const float* We = W + static_cast<size_t>(e) * N * K;
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;       // 16 x 16 threads, 4 columns x 4 rows each
+    const int ld_r = tid >> 2, ld_c = (tid & 3) * 4;  // 64 rows x 4 float4 per tile
+
+    int ar = row0 + ld_r; if (ar >= row_end) ar = row_end - 1;
+    int bn = n0 + ld_r;   if (bn >= N) bn = N - 1;
+    const float* a_src = A + static_cast<size_t>(ar) * K + ld_c;
+    const float* b_src = We + static_cast<size_t>(bn) * K + ld_c;
+
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        const float4 av = *reinterpret_cast<const float4*>(a_src + k0);
+        const float4 bv = *reinterpret_cast<const float4*>(b_src + k0);
+        As[ld_c + 0][ld_r] = av.x; As[ld_c + 1][ld_r] = av.y; As[ld_c + 2][ld_r] = av.z; As[ld_c + 3][ld_r] = av.w;
+        Bs[ld_c + 0][ld_r] = bv.x; Bs[ld_c + 1][ld_r] = bv.y; Bs[ld_c + 2][ld_r] = bv.z; Bs[ld_c + 3][ld_r] = bv.w;
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = row0 + ty * 4 + i;
+        if (r >= row_end) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n >= N) continue;
+            float val = acc[i][j] + (bias ? bias[static_cast<size_t>(e) * N + n] : 0.f);
+            if (GELU) val = gelu_erf(val);
+            C[static_cast<size_t>(r) * N + n] = val;
+        }
+    }
+}
+
+template <int BM, int BN, bool GELU>
+static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int N, int K,
+                                   const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
+                                   hipStream_t stream)
+{
+    const int n_tiles_n = (N + BN - 1) / BN;
+    const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
+    hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, GELU>), dim3(static_cast<unsigned>(m_tiles) * n_tiles_n), dim3(256),
+                       0, stream, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias,
+                       static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n);
+    return hipGetLastError();
+}
+
+template <bool GELU>
+static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bias, void* C, int N, int K,
+                                  const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
+                                  hipStream_t stream)
+{
+    const int n_tiles_n = (N + 63) / 64;
+    const int m_tiles = (max_rows + 63) / 64 + n_seg;
+    hipLaunchKernelGGL((ffn_gemm_f32_kernel<GELU>), dim3(static_cast<unsigned>(m_tiles) * n_tiles_n), dim3(256), 0,
+                       stream, static_cast<const float*>(A), static_cast<const float*>(W), bias,
+                       static_cast<float*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_expert_ffn(bool bf16, const void* x_packed, const int32_t* seg_offsets,
+                             const int32_t* seg_expert, int n_seg, int max_rows, int d, int F, const void* W1,
+                             const float* b1, const void* W2, const float* b2, void* h_packed, void* hidden,
+                             hipStream_t stream)
+{
+    if (max_rows == 0) return hipSuccess;
+    hipError_t err;
+    if (bf16) {
+        err = launch_gemm_bf16<128, 128, true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg,
+                                               max_rows, stream);
+        if (err != hipSuccess) return err;
+        return launch_gemm_bf16<128, 128, false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg,
+                                                 max_rows, stream);
+    }
+    err = launch_gemm_f32<true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream);
+    if (err != hipSuccess) return err;
+    return launch_gemm_f32<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream);
+}
+
+}  // namespace dicemoe

@@ -1,0 +1,37 @@
+// Host-side launchers of the gfx950 kernels (one per translation unit); the C-ABI in api.hip
+// validates arguments and calls these.  Every launcher only enqueues work on `stream`.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dicemoe {
+
+hipError_t launch_gate(bool bf16, const void* x, const void* Wg, const float* bg, int T_tok, int d, int E, int k,
+                       int renorm, float* scores, int32_t* idx, float* probs, float* logits, hipStream_t stream);
+
+// kind: 0 all, 1 Algorithm 4, 4 none (elementwise policies)
+hipError_t launch_refresh_simple(int kind, int T_tok, int k, int step_t, int stride_n, uint8_t* mask,
+                                 int32_t* n_refresh, hipStream_t stream);
+// exact top-m selection of tokens by scores[i*k + slot] (descending, ties to the lower token);
+// token_mode: selected tokens get all k slots; otherwise slots < slot are all refreshed, slot
+// `slot` follows the selection and later slots are not refreshed
+hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int slot, int m, bool token_mode,
+                                 int n_refresh_value, uint8_t* mask, int32_t* n_refresh, hipStream_t stream);
+
+hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const uint8_t* mask, int T_tok, int d,
+                           int E, int k, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
+                           int32_t* inv, hipStream_t stream);
+
+hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, const float* scores,
+                          const uint8_t* mask, int T_tok, int d, int k, void* H_cache, float* S_cache,
+                          int use_fresh, void* y, hipStream_t stream);
+
+hipError_t launch_expert_ffn(bool bf16, const void* x_packed, const int32_t* seg_offsets,
+                             const int32_t* seg_expert, int n_seg, int max_rows, int d, int F, const void* W1,
+                             const float* b1, const void* W2, const float* b2, void* h_packed, void* hidden,
+                             hipStream_t stream);
+
+hipError_t launch_ep_segments(const int32_t* recv_counts, int n_seg, int E_loc, int32_t* seg_offsets,
+                              int32_t* seg_expert, hipStream_t stream);
+
+}  // namespace dicemoe

@@ -1,0 +1,147 @@
+// Conditional Communication decision (supplement, Algorithm 4): which (token, slot) pairs are
+// recomputed this step and which reuse the cached expert output.
+//
+// ALL / NONE / ALG4 are elementwise.  The fraction policies need an exact top-m selection of
+// tokens by a float score with ties going to the lower token index; one workgroup does it with a
+// most-significant-digit radix select on the score's bit pattern (4 passes of 8 bits, LDS
+// histograms), then resolves ties at the threshold by a block-wide prefix count in index order.
+// Everything is integer work on the bit patterns, so the mask is reproducible bit for bit.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace dicemoe {
+
+__global__ __launch_bounds__(256) void refresh_simple_kernel(int kind, int N, int k, int off_step,
+                                                             uint8_t* __restrict__ mask,
+                                                             int32_t* __restrict__ n_refresh, int n_value)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p == 0) *n_refresh = n_value;
+    if (p >= N) return;
+    uint8_t m;
+    if (kind == 0) m = 1;                                   // every pair
+    else if (kind == 4) m = 0;                              // no pair
+    else m = ((p % k) == 0 || !off_step) ? 1 : 0;           // top-1 slot always, others on t mod n == 0
+    mask[p] = m;
+}
+
+// monotone map from float bits to unsigned: larger float <-> larger key
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / kWave;
+
+__global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float* __restrict__ scores, int T_tok,
+                                                                    int k, int slot, int m, int token_mode,
+                                                                    int n_value, uint8_t* __restrict__ mask,
+                                                                    int32_t* __restrict__ n_refresh)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sfx[2][256];
+    __shared__ uint32_t s_prefix, s_remaining;
+    __shared__ int wave_cnt[kSelWaves];
+    const int tid = threadIdx.x;
+    if (tid == 0) { *n_refresh = n_value; s_prefix = 0; s_remaining = static_cast<uint32_t>(m); }
+
+    const bool need_select = (m > 0 && m < T_tok);
+    if (need_select) {
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            const uint32_t prefix = s_prefix;       // both stable until the end of this pass
+            const uint32_t rem = s_remaining;
+            for (int i = tid; i < T_tok; i += kSelThreads) {
+                const uint32_t key = order_key(scores[static_cast<size_t>(i) * k + slot]);
+                const bool in_play = (pass == 0) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
+                if (in_play) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            // sfx[b] = number of in-play keys whose digit is larger than b (suffix sum, exclusive)
+            int cur = 0;
+            if (tid < 256) sfx[0][tid] = (tid < 255) ? hist[tid + 1] : 0u;
+            __syncthreads();
+            for (int step = 1; step < 256; step <<= 1) {
+                if (tid < 256) {
+                    uint32_t v = sfx[cur][tid];
+                    if (tid + step < 256) v += sfx[cur][tid + step];
+                    sfx[cur ^ 1][tid] = v;
+                }
+                cur ^= 1;
+                __syncthreads();
+            }
+            if (tid < 256) {
+                const uint32_t above = sfx[cur][tid];
+                if (above < rem && rem <= above + hist[tid]) {   // exactly one digit satisfies this
+                    s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
+                    s_remaining = rem - above;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+    const uint32_t thr = s_prefix;
+    const int admit_equal = static_cast<int>(s_remaining);  // keys equal to thr to admit, in index order
+    const int wave = tid / kWave;
+    int running = 0;
+    for (int base = 0; base < T_tok; base += kSelThreads) {
+        const int i = base + tid;
+        const bool valid = i < T_tok;
+        bool sel;
+        if (!need_select) {
+            sel = (m > 0);
+        } else {
+            const uint32_t key = valid ? order_key(scores[static_cast<size_t>(i) * k + slot]) : 0u;
+            const bool eq = valid && key == thr;
+            const uint64_t b = __ballot(eq);
+            if (lane_id() == 0) wave_cnt[wave] = __popcll(b);
+            __syncthreads();
+            int before = running + __popcll(b & lanemask_lt());
+            int total = 0;
+            for (int w = 0; w < kSelWaves; ++w) {
+                const int c = wave_cnt[w];
+                if (w < wave) before += c;
+                total += c;
+            }
+            running += total;
+            sel = valid && (key > thr || (eq && before < admit_equal));
+            __syncthreads();
+        }
+        if (valid) {
+            for (int j = 0; j < k; ++j) {
+                uint8_t v;
+                if (token_mode) v = sel ? 1 : 0;
+                else v = (j < slot) ? 1 : (j == slot ? (sel ? 1 : 0) : 0);
+                mask[static_cast<size_t>(i) * k + j] = v;
+            }
+        }
+    }
+}
+
+hipError_t launch_refresh_simple(int kind, int T_tok, int k, int step_t, int stride_n, uint8_t* mask,
+                                 int32_t* n_refresh, hipStream_t stream)
+{
+    const int N = T_tok * k;
+    int off_step = 0, n_value = 0;
+    if (kind == 0) n_value = N;
+    else if (kind == 4) n_value = 0;
+    else { off_step = (step_t % stride_n) != 0; n_value = off_step ? T_tok : N; }
+    const int blocks = N > 0 ? (N + 255) / 256 : 1;
+    hipLaunchKernelGGL(refresh_simple_kernel, dim3(blocks), dim3(256), 0, stream, kind, N, k, off_step, mask,
+                       n_refresh, n_value);
+    return hipGetLastError();
+}
+
+hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int slot, int m, bool token_mode,
+                                 int n_refresh_value, uint8_t* mask, int32_t* n_refresh, hipStream_t stream)
+{
+    hipLaunchKernelGGL(refresh_select_kernel, dim3(1), dim3(kSelThreads), 0, stream, scores, T_tok, k, slot, m,
+                       token_mode ? 1 : 0, n_refresh_value, mask, n_refresh);
+    return hipGetLastError();
+}
+
+}  // namespace dicemoe

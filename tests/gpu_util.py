@@ -1,0 +1,132 @@
+"""Helpers shared by the GPU parity tests: upload seeded inputs, run the HIP path through the
+C-ABI binding, fetch results as numpy, and the tolerance checks.
+
+Tolerances (derived in the design document):
+  * float storage: outputs within 1e-5 relative (max-abs against the largest reference magnitude,
+    and relative L2).
+  * bf16 storage: max-abs 2e-2 and relative L2 1e-2 end to end; a single kernel whose only
+    rounding is its bf16 output is held to one bf16 half-ulp (2^-8 relative) plus float noise.
+  * integer results (indices, counts, permutation, mask): bit-exact.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import moe_oracle as O
+from paper_2411_16786_amd import binding as B
+from paper_2411_16786_amd import workloads as WL
+
+DEV = "cuda"
+
+
+def to_dev(a, dtype: str):
+    """float32 numpy array (values exact in ``dtype``) -> device tensor of the storage type."""
+    if a is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    if dtype == "bf16":
+        t = t.to(torch.bfloat16)
+    return t.to(DEV).contiguous()
+
+
+def f32_dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+
+
+def i32_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def u8_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(DEV)
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> numpy; bf16 is widened to float32 (exact)."""
+    t = t.detach()
+    if t.dtype == torch.bfloat16:
+        t = t.to(torch.float32)
+    return t.cpu().numpy()
+
+
+def small_inputs(seed, T, d, E, F, dtype, bias=True, w_std=0.05):
+    r = np.random.Generator(np.random.PCG64(seed))
+    st = lambda a: WL.to_storage(a, dtype)
+    x = st(r.standard_normal((T, d), dtype=np.float32))
+    Wg = st(r.standard_normal((E, d), dtype=np.float32) / np.float32(np.sqrt(d)))
+    bg = (r.standard_normal(E, dtype=np.float32) * np.float32(0.5)) if bias else None
+    W1 = st(r.standard_normal((E, F, d), dtype=np.float32) * np.float32(w_std))
+    W2 = st(r.standard_normal((E, d, F), dtype=np.float32) * np.float32(w_std))
+    b1 = (r.standard_normal((E, F), dtype=np.float32) * np.float32(0.1)) if bias else None
+    b2 = (r.standard_normal((E, d), dtype=np.float32) * np.float32(0.1)) if bias else None
+    return x, Wg, bg, W1, b1, W2, b2
+
+
+def topk_margin(z: np.ndarray, k: int) -> float:
+    """Smallest gap between neighbouring logits among each token's k+1 largest."""
+    zs = -np.sort(-z, axis=1)
+    kk = min(k + 1, z.shape[1])
+    if kk < 2:
+        return np.inf
+    return float(np.min(zs[:, :kk - 1] - zs[:, 1:kk]))
+
+
+def pick_layer(cfg: int, layer: int = 0, T=None, with_experts=True, margin=1e-4, k=None):
+    """Seeded inputs of a workload whose routing is free of near-ties (so that float and double
+    logits must agree on the top-K); the seed is bumped until that holds."""
+    for bump in range(20):
+        li = WL.make_layer(cfg, layer=layer, bump=bump, with_experts=False, T=T)
+        z = O.router_logits(li.x, li.Wg, li.bg)
+        if topk_margin(z, li.cfg.k if k is None else k) >= margin:
+            if with_experts:
+                li = WL.make_layer(cfg, layer=layer, bump=bump, with_experts=True, T=T)
+            return li, z
+    raise AssertionError("no seed without near-ties found")
+
+
+def assert_close_storage(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", end_to_end=True):
+    got = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    err = np.abs(got - ref)
+    scale = max(np.abs(ref).max(), 1e-30)
+    rel_l2 = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+    if dtype == "f32":
+        assert err.max() <= 1e-5 * scale, f"{what}: max-abs {err.max():.3e} vs scale {scale:.3e}"
+        assert rel_l2 <= 1e-5, f"{what}: rel-L2 {rel_l2:.3e}"
+    elif end_to_end:
+        assert err.max() <= 2e-2, f"{what}: max-abs {err.max():.3e}"
+        assert rel_l2 <= 1e-2, f"{what}: rel-L2 {rel_l2:.3e}"
+    else:
+        # one bf16 rounding of the result: half an ulp = 2^-9 relative, plus float accumulation noise
+        tol = np.abs(ref) * 2.0 ** -8 + 1e-6 * scale
+        bad = err > tol
+        assert not bad.any(), f"{what}: {bad.sum()} elements beyond one bf16 rounding, worst {err.max():.3e}"
+
+
+class GpuLayer:
+    """Uploads one layer's inputs and runs the HIP path stage by stage."""
+
+    def __init__(self, x, Wg, bg, W1, b1, W2, b2, k, dtype, T_max=None, renorm=False, with_cache=False):
+        self.dtype = dtype
+        T, d = x.shape
+        E = Wg.shape[0]
+        F = W1.shape[1] if W1 is not None else d * 4
+        self.ctx = B.Context(T_max or T, d, F, E, k, dtype, renorm_topk=renorm)
+        self.x = to_dev(x, dtype)
+        self.Wg = to_dev(Wg, dtype)
+        self.bg = f32_dev(bg)
+        self.W1 = to_dev(W1, dtype)
+        self.W2 = to_dev(W2, dtype)
+        self.b1 = f32_dev(b1)
+        self.b2 = f32_dev(b2)
+        self.buf = B.LayerBuffers(self.ctx, DEV, with_cache=with_cache, with_debug=True)
+
+    def forward(self, policy=None, x=None):
+        y = B.moe_layer_forward(self.ctx, self.buf, self.x if x is None else x, self.Wg, self.bg,
+                                self.W1, self.b1, self.W2, self.b2, policy)
+        torch.cuda.synchronize()
+        return y

@@ -1,0 +1,107 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every entry point
+the header declares, validates shapes and policies, and reports errors before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2411_16786_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "dice_moe.h")
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_entry_point():
+    names = declared_functions()
+    assert {"moe_gate", "moe_dispatch", "moe_expert_ffn", "moe_combine", "moe_conditional_refresh"} <= set(names)
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_struct_layouts_match_the_header():
+    src = open(HEADER).read()
+    shape_fields = re.search(r"typedef struct \{([^{}]*)\} moe_shape;", src, re.S).group(1)
+    shape_fields = re.sub(r"/\*.*?\*/", "", shape_fields, flags=re.S)
+    names = re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*[,;]", shape_fields)
+    assert names == [f[0] for f in B.MoeShape._fields_]
+    pol_fields = re.search(r"typedef struct \{([^{}]*)\} moe_policy;", src, re.S).group(1)
+    pol_fields = re.sub(r"/\*.*?\*/", "", pol_fields, flags=re.S)
+    names = re.findall(r"\b([A-Za-z_][A-Za-z0-9_]*)\s*[,;]", pol_fields)
+    assert names == [f[0] for f in B.MoePolicy._fields_]
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(T_max=64, d=64, F=256, E=4, k=2, dtype="f32"), 0),
+    (dict(T_max=64, d=64, F=256, E=4, k=5, dtype="f32"), B.MOE_ERR_SHAPE),       # k > E
+    (dict(T_max=64, d=64, F=256, E=65, k=2, dtype="f32"), B.MOE_ERR_SHAPE),      # E > 64
+    (dict(T_max=64, d=60, F=256, E=4, k=2, dtype="f32"), B.MOE_ERR_SHAPE),       # d % 16
+    (dict(T_max=64, d=96, F=256, E=4, k=2, dtype="bf16"), B.MOE_ERR_SHAPE),      # d % 64 for bf16
+    (dict(T_max=-1, d=64, F=256, E=4, k=2, dtype="f32"), B.MOE_ERR_SHAPE),
+    (dict(T_max=1 << 22, d=2048, F=8192, E=16, k=2, dtype="bf16"), B.MOE_ERR_SHAPE),  # index overflow
+])
+def test_create_validates_shape(kw, status):
+    if status == 0:
+        ctx = B.Context(**kw)
+        assert ctx.workspace_bytes() >= kw["T_max"] * kw["k"] * kw["F"] * 4
+    else:
+        with pytest.raises(B.MoeError) as ei:
+            B.Context(**kw)
+        assert ei.value.status == status
+
+
+def test_create_rejects_unknown_dtype_and_null():
+    L = B.lib()
+    h = ctypes.c_void_p()
+    shape = B.MoeShape(64, 64, 256, 4, 2, 7, 0)
+    assert L.moe_create(ctypes.byref(h), ctypes.byref(shape)) == B.MOE_ERR_DTYPE
+    assert L.moe_create(None, ctypes.byref(shape)) == B.MOE_ERR_NULL
+    assert L.moe_destroy(None) == B.MOE_ERR_NULL
+    assert L.moe_status_string(B.MOE_ERR_CACHE_COLD) == b"MOE_ERR_CACHE_COLD"
+
+
+def test_host_detectable_errors_return_before_any_launch():
+    L = B.lib()
+    ctx = B.Context(T_max=64, d=64, F=256, E=4, k=2, dtype="f32")
+    h = ctx._h
+    one = ctypes.c_void_p(16)       # a non-null dummy address; never dereferenced on these paths
+    # null pointers
+    assert L.moe_gate(h, None, one, None, 8, one, one, None, None, None) == B.MOE_ERR_NULL
+    assert b"moe_gate" in L.moe_last_error(h)
+    # T out of range
+    assert L.moe_gate(h, one, one, None, 65, one, one, None, None, None) == B.MOE_ERR_SHAPE
+    assert L.moe_dispatch(h, one, one, None, -1, one, one, one, one, one, None, None) == B.MOE_ERR_SHAPE
+    # policies
+    pol = B.MoePolicy(B.REFRESH_ALG4, 1, 0, 0, 0)
+    assert L.moe_conditional_refresh(h, one, one, 8, ctypes.byref(pol), one, one, None, None) == B.MOE_ERR_POLICY
+    pol = B.MoePolicy(B.REFRESH_FRACTION_TOKEN, 0, 1, 9, 0)
+    assert L.moe_conditional_refresh(h, one, one, 8, ctypes.byref(pol), one, one, None, None) == B.MOE_ERR_POLICY
+    pol = B.MoePolicy(B.REFRESH_FRACTION_PAIR, 0, 1, 17, 0)
+    assert L.moe_conditional_refresh(h, one, one, 8, ctypes.byref(pol), one, one, None, None) == B.MOE_ERR_POLICY
+    pol = B.MoePolicy(99, 0, 1, 0, 0)
+    assert L.moe_conditional_refresh(h, one, one, 8, ctypes.byref(pol), one, one, None, None) == B.MOE_ERR_POLICY
+    # partial refresh with no cache
+    assert L.moe_combine(h, one, one, one, one, 8, None, None, 0, one, None) == B.MOE_ERR_CACHE_COLD
+    # FFN: segments, rows, workspace
+    assert L.moe_expert_ffn(h, one, one, one, 0, 8, one, None, one, None, one, one, None) == B.MOE_ERR_SHAPE
+    assert L.moe_expert_ffn(h, one, one, one, 4, 129, one, None, one, None, one, one, None) == B.MOE_ERR_SHAPE
+    assert L.moe_expert_ffn(h, one, one, one, 4, 8, one, None, one, None, one, None, None) == B.MOE_ERR_WORKSPACE
+    assert L.moe_ep_segments(h, one, 4, 8, one, one, None) == B.MOE_ERR_SHAPE     # E_loc > E
+    # T = 0 launches nothing
+    assert L.moe_gate(h, one, one, None, 0, one, one, None, None, None) == B.MOE_OK
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    ctx = B.Context(T_max=8, d=64, F=256, E=4, k=2, dtype="f32")
+    x = torch.zeros(8, 64)
+    with pytest.raises(ValueError):
+        ctx.moe_gate(x, x, None, x, x)

@@ -1,0 +1,511 @@
+"""Parity of the HIP path (through the C-ABI binding) against the CPU oracle, stage by stage and
+end to end, on the same seeded inputs.  Integer results are bit-exact; floating-point results
+are held to the tolerances of tests/gpu_util.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2411_16786_amd import binding as B
+from paper_2411_16786_amd import workloads as WL
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ----------------------------------------------------------------------------- gate
+GATE_CASES = [
+    # (name, T, d, E, k, dtype, bias, renorm)
+    ("tiny-f32", 64, 64, 4, 2, "f32", False, False),
+    ("ragged-f32", 131, 80, 7, 3, "f32", True, True),
+    ("s-bf16", 2048, 384, 16, 2, "bf16", False, False),
+    ("xl-bf16", 1000, 1152, 8, 2, "bf16", True, False),
+    ("k-equals-E", 70, 128, 5, 5, "bf16", True, False),
+    ("E64-wide", 300, 2048, 64, 6, "bf16", True, False),     # router rows too large for LDS
+    ("E32", 257, 256, 32, 4, "bf16", False, True),
+    ("one-token", 1, 64, 4, 1, "f32", False, False),
+]
+
+
+@pytest.mark.parametrize("case", GATE_CASES, ids=[c[0] for c in GATE_CASES])
+def test_gate_against_oracle(case):
+    name, T, d, E, k, dtype, bias, renorm = case
+    say(f"gate case {name}")
+    x, Wg, bg, *_ = G.small_inputs(11, T, d, E, 64, dtype, bias=bias)
+    ctx = B.Context(T, d, 64, E, k, dtype, renorm_topk=renorm)
+    scores = torch.empty((T, k), dtype=torch.float32, device=G.DEV)
+    idx = torch.empty((T, k), dtype=torch.int32, device=G.DEV)
+    probs = torch.empty((T, E), dtype=torch.float32, device=G.DEV)
+    logits = torch.empty((T, E), dtype=torch.float32, device=G.DEV)
+    ctx.moe_gate(G.to_dev(x, dtype), G.to_dev(Wg, dtype), G.f32_dev(bg), scores, idx, probs, logits)
+    torch.cuda.synchronize()
+    z_gpu, idx_gpu, s_gpu, p_gpu = map(G.to_np, (logits, idx, scores, probs))
+
+    z = O.router_logits(x, Wg, bg)
+    assert np.abs(z_gpu - z).max() <= 2e-5 * max(1.0, np.abs(z).max())
+    # integer stage of the oracle on the GPU's own float logits: must agree bit for bit
+    idx_on_gpu_logits = O.topk(z_gpu.astype(np.float64), k)
+    np.testing.assert_array_equal(idx_gpu, idx_on_gpu_logits)
+    # softmax / scores of the oracle on the same routing
+    p, s = O.scores(z, idx_gpu, renorm_topk=renorm)
+    np.testing.assert_allclose(p_gpu, p, rtol=5e-5, atol=1e-9)
+    np.testing.assert_allclose(s_gpu, s, rtol=5e-5, atol=1e-9)
+    # wherever double logits leave no near-tie, the routing from x itself agrees too
+    idx_ref = O.topk(z, k)
+    zs = -np.sort(-z, axis=1)
+    kk = min(k + 1, E)
+    safe = np.min(zs[:, :kk - 1] - zs[:, 1:kk], axis=1) > 1e-4 if kk >= 2 else np.ones(T, bool)
+    assert safe.mean() > 0.98
+    np.testing.assert_array_equal(idx_gpu[safe], idx_ref[safe])
+
+
+def test_gate_exact_ties_go_to_the_lower_expert():
+    # duplicated router rows give exactly equal logits
+    T, d, E, k = 40, 64, 6, 3
+    x, Wg, bg, *_ = G.small_inputs(12, T, d, E, 64, "bf16", bias=False)
+    Wg[3] = Wg[1]
+    Wg[5] = Wg[0]
+    ctx = B.Context(T, d, 64, E, k, "bf16")
+    scores = torch.empty((T, k), dtype=torch.float32, device=G.DEV)
+    idx = torch.empty((T, k), dtype=torch.int32, device=G.DEV)
+    logits = torch.empty((T, E), dtype=torch.float32, device=G.DEV)
+    ctx.moe_gate(G.to_dev(x, "bf16"), G.to_dev(Wg, "bf16"), None, scores, idx, None, logits)
+    torch.cuda.synchronize()
+    z_gpu = G.to_np(logits)
+    assert (z_gpu[:, 3] == z_gpu[:, 1]).all() and (z_gpu[:, 5] == z_gpu[:, 0]).all()
+    np.testing.assert_array_equal(G.to_np(idx), O.topk(z_gpu.astype(np.float64), k))
+
+
+# ----------------------------------------------------------------------------- refresh mask
+def gpu_mask(ctx, s_dev, policy):
+    T, k = s_dev.shape
+    mask = torch.full((T, k), 7, dtype=torch.uint8, device=G.DEV)
+    n = torch.full((1,), -5, dtype=torch.int32, device=G.DEV)
+    ws = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=G.DEV)
+    ctx.moe_conditional_refresh(s_dev, None, policy, mask, n, ws)
+    torch.cuda.synchronize()
+    return G.to_np(mask), int(n.item())
+
+
+@pytest.mark.parametrize("T,k", [(1, 2), (63, 2), (1024, 2), (1025, 2), (2049, 3), (8192, 2), (5000, 1)])
+def test_refresh_mask_bit_exact(T, k):
+    say(f"refresh mask T={T} k={k}")
+    r = np.random.Generator(np.random.PCG64(100 + T))
+    s = np.sort(r.random((T, k), dtype=np.float32), axis=1)[:, ::-1].copy()
+    if T > 100:                      # exact ties across the selection boundary
+        s[T // 3: T // 3 + 40, 0] = s[T // 3, 0]
+        s[5:25, k - 1] = s[5, k - 1]
+    ctx = B.Context(T, 64, 64, 4, k, "f32") if k <= 4 else None
+    s_dev = G.f32_dev(s)
+    s64 = s.astype(np.float64)
+    pols = [B.Policy(B.REFRESH_ALL), B.Policy(B.REFRESH_NONE)]
+    for t in range(4):
+        for n in (1, 2, 3):
+            pols.append(B.Policy(B.REFRESH_ALG4, step_t=t, stride_n=n))
+    for n_units in sorted({0, 1, T // 4, T // 3 + 17 if T > 100 else T // 2, T // 2, (3 * T) // 4, T - 1, T} - {-1}):
+        if 0 <= n_units <= T:
+            pols.append(B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=n_units))
+    for n_units in sorted({0, 1, T // 2, T - 1, T, T + 1, T + T // 3, T * k - 1, T * k}):
+        if 0 <= n_units <= T * k:
+            pols.append(B.Policy(B.REFRESH_FRACTION_PAIR, n_units=n_units))
+    for pol in pols:
+        m_gpu, n_gpu = gpu_mask(ctx, s_dev, pol)
+        m_ref, R = O.refresh_mask(s64, pol.kind, pol.step_t, pol.stride_n, pol.n_units)
+        np.testing.assert_array_equal(m_gpu, m_ref, err_msg=str(pol))
+        assert n_gpu == R == int(m_ref.sum()), pol
+
+
+# ----------------------------------------------------------------------------- dispatch
+@pytest.mark.parametrize("T,E,k,d,dtype,masked", [
+    (64, 4, 2, 64, "f32", False),
+    (301, 8, 2, 128, "bf16", True),
+    (2048, 16, 2, 384, "bf16", False),
+    (1000, 64, 6, 64, "bf16", True),
+    (4096, 8, 2, 1152, "bf16", False),
+    (8192, 8, 2, 1152, "bf16", True),
+    (17, 3, 3, 64, "f32", True),
+    (1, 4, 2, 64, "bf16", False),
+])
+def test_dispatch_bit_exact(T, E, k, d, dtype, masked):
+    say(f"dispatch T={T} E={E} k={k} d={d} {dtype} masked={masked}")
+    r = np.random.Generator(np.random.PCG64(200 + T + E))
+    x = WL.to_storage(r.standard_normal((T, d), dtype=np.float32), dtype)
+    # skewed routing, distinct experts per token
+    z = r.standard_normal((T, E)) + np.log(WL.zipf_weights(E, 1.2))
+    idx = O.topk(z, k)
+    mask = (r.random((T, k)) < 0.5).astype(np.uint8) if masked else None
+    ctx = B.Context(T, d, 64, E, k, dtype)
+    buf = B.LayerBuffers(ctx, G.DEV)
+    buf.x_packed.fill_(-77.0)
+    ctx.moe_dispatch(G.to_dev(x, dtype), G.i32_dev(idx), None if mask is None else G.u8_dev(mask),
+                     buf.x_packed, buf.counts, buf.offsets, buf.perm, buf.inv, buf.workspace)
+    torch.cuda.synchronize()
+    counts, offsets, perm, inv = O.dispatch(idx, mask, E)
+    R = perm.shape[0]
+    np.testing.assert_array_equal(G.to_np(buf.counts), counts)
+    np.testing.assert_array_equal(G.to_np(buf.offsets), offsets)
+    perm_gpu = G.to_np(buf.perm)
+    np.testing.assert_array_equal(perm_gpu[:R], perm)
+    assert (perm_gpu[R:] == -1).all()
+    np.testing.assert_array_equal(G.to_np(buf.inv).reshape(T, k), inv)
+    xp = G.to_np(buf.x_packed)
+    np.testing.assert_array_equal(xp[:R], O.pack_rows(x, perm, k))       # rows copied bit for bit
+    assert (xp[R:] == -77.0).all()                                       # rows beyond R untouched
+
+
+def test_dispatch_nothing_refreshed():
+    T, E, k, d = 100, 4, 2, 64
+    idx = O.topk(np.random.default_rng(1).standard_normal((T, E)), k)
+    ctx = B.Context(T, d, 64, E, k, "bf16")
+    buf = B.LayerBuffers(ctx, G.DEV)
+    x = torch.zeros((T, d), dtype=torch.bfloat16, device=G.DEV)
+    ctx.moe_dispatch(x, G.i32_dev(idx), G.u8_dev(np.zeros((T, k), np.uint8)), buf.x_packed, buf.counts,
+                     buf.offsets, buf.perm, buf.inv, buf.workspace)
+    torch.cuda.synchronize()
+    assert G.to_np(buf.counts).sum() == 0 and (G.to_np(buf.offsets) == 0).all()
+    assert (G.to_np(buf.perm) == -1).all() and (G.to_np(buf.inv) == -1).all()
+
+
+# ----------------------------------------------------------------------------- expert FFN
+FFN_CASES = [
+    # (name, rows per segment, d, F, dtype, bias)
+    ("f32-tiny", [30, 0, 41, 57], 64, 256, "f32", False),
+    ("f32-bias-ragged", [1, 65, 64, 130], 48, 80, "f32", True),
+    ("bf16-ragged", [129, 0, 300, 1, 127, 256], 128, 320, "bf16", True),
+    ("bf16-s-shape", [200, 310, 64, 450], 384, 1536, "bf16", False),
+    ("bf16-one-row", [1], 64, 64, "bf16", True),
+]
+
+
+@pytest.mark.parametrize("case", FFN_CASES, ids=[c[0] for c in FFN_CASES])
+def test_expert_ffn_against_oracle(case):
+    name, seg_rows, d, F, dtype, bias = case
+    say(f"ffn case {name}")
+    E = len(seg_rows)
+    rows = int(sum(seg_rows))
+    _, _, _, W1, b1, W2, b2 = G.small_inputs(31, 4, d, E, F, dtype, bias=bias)
+    r = np.random.Generator(np.random.PCG64(32))
+    xp = WL.to_storage(r.standard_normal((rows, d), dtype=np.float32), dtype)
+    # segments in a permuted expert order: the segment table, not the position, picks the expert
+    seg_expert = np.roll(np.arange(E, dtype=np.int32), 1)
+    seg_offsets = np.concatenate([[0], np.cumsum(seg_rows)]).astype(np.int32)
+    ctx = B.Context(rows + 8, d, F, E, 1, dtype)
+    h = torch.full((rows + 8, d), 9.0, dtype=ctx.torch_dtype, device=G.DEV)
+    xp_dev = torch.zeros((rows + 8, d), dtype=ctx.torch_dtype, device=G.DEV)
+    xp_dev[:rows] = G.to_dev(xp, dtype)
+    ws = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=G.DEV)
+    ctx.moe_expert_ffn(xp_dev, G.i32_dev(seg_offsets), G.i32_dev(seg_expert), rows + 8, G.to_dev(W1, dtype),
+                       G.f32_dev(b1), G.to_dev(W2, dtype), G.f32_dev(b2), h, ws)
+    torch.cuda.synchronize()
+    h_gpu = G.to_np(h)
+    h_ref = O.expert_ffn(xp, seg_offsets, seg_expert, W1, b1, W2, b2)
+    G.assert_close_storage(h_gpu[:rows], h_ref, dtype, name)
+    assert (h_gpu[rows:] == 9.0).all()          # rows outside every segment are left untouched
+
+
+# ----------------------------------------------------------------------------- combine
+@pytest.mark.parametrize("T,k,d,dtype", [(64, 2, 64, "f32"), (333, 3, 128, "bf16"), (4096, 2, 1152, "bf16")])
+def test_combine_against_oracle_on_the_same_rows(T, k, d, dtype):
+    say(f"combine T={T} k={k} d={d} {dtype}")
+    r = np.random.Generator(np.random.PCG64(40 + T))
+    N = T * k
+    h = WL.to_storage(r.standard_normal((N, d), dtype=np.float32), dtype)
+    s = r.random((T, k), dtype=np.float32)
+    inv = r.permutation(N).astype(np.int32).reshape(T, k)
+    ctx = B.Context(T, d, 64, max(k, 4), k, dtype)
+    y = torch.empty((T, d), dtype=ctx.torch_dtype, device=G.DEV)
+    ctx.moe_combine(G.to_dev(h, dtype), G.i32_dev(inv), G.f32_dev(s), None, None, None, False, y)
+    torch.cuda.synchronize()
+    y_ref = O.combine(h.astype(np.float64), inv, s.astype(np.float64), None)
+    G.assert_close_storage(G.to_np(y), y_ref, dtype, "combine", end_to_end=False)
+
+    # with a mask: fresh rows from the packed buffer, reused rows and scores from the cache
+    mask = (r.random((T, k)) < 0.5).astype(np.uint8)
+    Hc = WL.to_storage(r.standard_normal((T, k, d), dtype=np.float32), dtype)
+    Sc = r.random((T, k), dtype=np.float32)
+    for use_fresh in (False, True):
+        Hc_dev, Sc_dev = G.to_dev(Hc, dtype), G.f32_dev(Sc)
+        ctx.moe_combine(G.to_dev(h, dtype), G.i32_dev(inv), G.f32_dev(s), G.u8_dev(mask), Hc_dev, Sc_dev,
+                        use_fresh, y)
+        torch.cuda.synchronize()
+        Hc64, Sc64 = Hc.astype(np.float64), Sc.astype(np.float64)
+        y_ref = O.combine(h.astype(np.float64), inv, s.astype(np.float64), mask, Hc64, Sc64, use_fresh)
+        G.assert_close_storage(G.to_np(y), y_ref, dtype, "combine+cache", end_to_end=False)
+        # write-through is a copy: bit-exact; untouched entries unchanged
+        np.testing.assert_array_equal(G.to_np(Hc_dev), Hc64.astype(np.float32))
+        np.testing.assert_array_equal(G.to_np(Sc_dev), Sc64.astype(np.float32))
+
+
+# ----------------------------------------------------------------------------- whole layer
+def check_layer(li_x, Wg, bg, W1, b1, W2, b2, k, dtype, name, renorm=False):
+    g = G.GpuLayer(li_x, Wg, bg, W1, b1, W2, b2, k, dtype, renorm=renorm)
+    y = G.to_np(g.forward())
+    ref = O.moe_layer(li_x, Wg, bg, W1, b1, W2, b2, k, renorm_topk=renorm)
+    np.testing.assert_array_equal(G.to_np(g.buf.expert_idx), ref.idx)
+    np.testing.assert_array_equal(G.to_np(g.buf.counts), ref.counts)
+    np.testing.assert_array_equal(G.to_np(g.buf.offsets), ref.offsets)
+    np.testing.assert_array_equal(G.to_np(g.buf.perm)[:ref.R], ref.perm)
+    np.testing.assert_array_equal(G.to_np(g.buf.inv).reshape(ref.inv.shape), ref.inv)
+    np.testing.assert_allclose(G.to_np(g.buf.scores), ref.s, rtol=5e-5)
+    G.assert_close_storage(G.to_np(g.buf.h_packed)[:ref.R], ref.h_packed, dtype, name + " h")
+    G.assert_close_storage(y, ref.y, dtype, name + " y")
+    # determinism: a second run is bit-identical
+    y2 = G.to_np(g.forward())
+    np.testing.assert_array_equal(y, y2)
+    return g, ref
+
+
+def test_layer_config1_tiny_fp32():
+    li, _ = G.pick_layer(1)
+    say(f"config 1 seed {li.seed}")
+    check_layer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, 2, "f32", "cfg1")
+
+
+def test_layer_config1_invariant_variants():
+    # k = E (dense sum), identical experts, renormalised scores, biases
+    x, Wg, bg, W1, b1, W2, b2 = G.small_inputs(51, 64, 64, 4, 256, "f32", bias=True)
+    check_layer(x, Wg, bg, W1, b1, W2, b2, 4, "f32", "k=E")
+    check_layer(x, Wg, bg, W1, b1, W2, b2, 2, "f32", "renorm", renorm=True)
+    W1[:] = W1[0]; W2[:] = W2[0]; b1[:] = b1[0]; b2[:] = b2[0]
+    g, ref = check_layer(x, Wg, bg, W1, b1, W2, b2, 2, "f32", "identical experts")
+    one = O.expert_ffn(x, [0, 64], [0], W1, b1, W2, b2)
+    G.assert_close_storage(G.to_np(g.buf.y), one * ref.s.sum(axis=1, keepdims=True), "f32", "expert(x)*sum(gates)")
+
+
+def test_layer_config2_small_bf16():
+    li, _ = G.pick_layer(2)
+    say(f"config 2 seed {li.seed}")
+    g, ref = check_layer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, 2, "bf16", "cfg2")
+    load = ref.counts / ref.counts.mean()
+    assert load.max() < 1.5          # near-uniform load
+
+
+def sampled_layer_check(g, ref_idx_stage, li, k, name, n_rows=96, n_tok=64, seed=0):
+    """Full-size check: integer stages in full, FFN rows and output tokens on a sample."""
+    c = li.cfg
+    z, idx, s, counts, offsets, perm, inv = ref_idx_stage
+    np.testing.assert_array_equal(G.to_np(g.buf.expert_idx), idx)
+    np.testing.assert_array_equal(G.to_np(g.buf.counts), counts)
+    np.testing.assert_array_equal(G.to_np(g.buf.offsets), offsets)
+    R = perm.shape[0]
+    np.testing.assert_array_equal(G.to_np(g.buf.perm)[:R], perm)
+    np.testing.assert_array_equal(G.to_np(g.buf.inv).reshape(inv.shape), inv)
+    np.testing.assert_allclose(G.to_np(g.buf.scores), s, rtol=5e-5)
+    xp_gpu = G.to_np(g.buf.x_packed)[:R]
+    np.testing.assert_array_equal(xp_gpu, li.x[perm // k])
+    r = np.random.Generator(np.random.PCG64(seed))
+    # sampled tokens: all their pairs go through the oracle's expert, then its combine
+    toks = np.sort(r.choice(li.x.shape[0], size=n_tok, replace=False)).astype(np.int32)
+    # always include the first and last row of every expert's segment (tile edges, ragged tails)
+    edge_rows = np.unique(np.concatenate([offsets[:-1][counts > 0], offsets[1:][counts > 0] - 1]))
+    rows = np.unique(np.concatenate([inv[toks].reshape(-1), edge_rows,
+                                     r.choice(R, size=n_rows, replace=False)])).astype(np.int32)
+    h_ref = O.expert_ffn(xp_gpu, offsets, np.arange(c.E), li.W1, None, li.W2, None, rows_sel=rows)
+    h_gpu = G.to_np(g.buf.h_packed)
+    G.assert_close_storage(h_gpu[rows], h_ref, c.dtype, name + " h rows")
+    h_sparse = np.zeros((R, c.d))
+    h_sparse[rows] = h_ref
+    y_ref = O.combine(h_sparse, inv, s, None, tokens_sel=toks)
+    G.assert_close_storage(G.to_np(g.buf.y)[toks], y_ref, c.dtype, name + " y tokens")
+
+
+def oracle_index_stages(li, k, z=None):
+    z = O.router_logits(li.x, li.Wg, li.bg) if z is None else z
+    idx = O.topk(z, k)
+    _, s = O.scores(z, idx)
+    counts, offsets, perm, inv = O.dispatch(idx, None, li.cfg.E)
+    return z, idx, s, counts, offsets, perm, inv
+
+
+@pytest.mark.parametrize("layer", [0, 27])
+def test_layer_config3_xl_full_size_sampled(layer):
+    li, z = G.pick_layer(3, layer=layer)
+    say(f"config 3 layer {layer} seed {li.seed}")
+    g = G.GpuLayer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, 2, "bf16")
+    g.forward()
+    st = oracle_index_stages(li, 2, z)
+    load = st[3] / st[3].mean()
+    say(f"  expert load max/mean = {load.max():.2f}")
+    assert 1.2 < load.max() < 4.0            # moderately uneven
+    sampled_layer_check(g, st, li, 2, f"cfg3 layer {layer}", seed=layer)
+
+
+# ----------------------------------------------------------------------------- conditional refresh, two steps
+def run_two_steps(T, cfg=4, fractions=(0.25, 0.5, 0.75, 1.0), sample=None):
+    li, _ = G.pick_layer(cfg, T=T)
+    c = li.cfg
+    k = c.k
+    x1 = None
+    for bump in range(20):                    # step-t activations also free of near-ties
+        x1 = WL.next_step_x(cfg, li.x, bump=bump)
+        z1 = O.router_logits(x1, li.Wg, li.bg)
+        if G.topk_margin(z1, k) >= 1e-4:
+            break
+    say(f"two steps: T={T} seed {li.seed} step bump {bump}")
+    return li, x1, z1
+
+
+def test_conditional_refresh_two_steps_small_full_parity():
+    T = 1024
+    li, x1, z1 = run_two_steps(T)
+    c, k, d = li.cfg, li.cfg.k, li.cfg.d
+    # shrink the expert width so that the oracle runs every row in seconds
+    F = 256
+    W1 = li.W1[:, :F, :].copy()
+    W2 = li.W2[:, :, :F].copy()
+    g = G.GpuLayer(li.x, li.Wg, li.bg, W1, None, W2, None, k, "bf16", with_cache=True)
+    x1_dev = G.to_dev(x1, "bf16")
+
+    def oracle_step0():
+        H = np.zeros((T, k, d)); S = np.zeros((T, k))
+        r0 = O.moe_layer(li.x, li.Wg, li.bg, W1, None, W2, None, k, policy=O.REFRESH_ALL, H_cache=H, S_cache=S)
+        return r0, H, S
+
+    r0, H0, S0 = oracle_step0()
+    sync1 = O.moe_layer(x1, li.Wg, li.bg, W1, None, W2, None, k)
+    changed = (sync1.idx != r0.idx).any(axis=1).mean()
+    say(f"  routing changed for {100 * changed:.1f}% of tokens between the two steps")
+
+    policies = [B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=int(np.floor(f * T + 0.5))) for f in (0.25, 0.5, 0.75, 1.0)]
+    policies += [B.Policy(B.REFRESH_ALG4, step_t=1, stride_n=2), B.Policy(B.REFRESH_FRACTION_PAIR, n_units=T),
+                 B.Policy(B.REFRESH_NONE), B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=T // 2, use_fresh_scores=True)]
+    for pol in policies:
+        # step t-1: synchronous, fills the cache
+        y0 = G.to_np(g.forward(B.Policy(B.REFRESH_ALL)))
+        G.assert_close_storage(y0, r0.y, "bf16", "step0 y")
+        Hc0, Sc0 = G.to_np(g.buf.H_cache).copy(), G.to_np(g.buf.S_cache).copy()
+        G.assert_close_storage(Hc0.reshape(T * k, d), H0.reshape(T * k, d), "bf16", "step0 cache")
+        # step t: partial refresh
+        y1 = G.to_np(g.forward(pol, x=x1_dev))
+        H, S = H0.copy(), S0.copy()
+        r1 = O.moe_layer(x1, li.Wg, li.bg, W1, None, W2, None, k, policy=pol.kind, step_t=pol.step_t,
+                         stride_n=pol.stride_n, n_units=pol.n_units, H_cache=H, S_cache=S,
+                         use_fresh_scores=pol.use_fresh_scores)
+        # the mask from the GPU's own float scores, by the oracle: bit-exact
+        s_gpu = G.to_np(g.buf.scores).astype(np.float64)
+        m_ref_gpu_scores, R = O.refresh_mask(s_gpu, pol.kind, pol.step_t, pol.stride_n, pol.n_units)
+        m_gpu = G.to_np(g.buf.mask)
+        np.testing.assert_array_equal(m_gpu, m_ref_gpu_scores, err_msg=str(pol))
+        assert int(g.buf.n_refresh.item()) == R
+        if np.array_equal(m_gpu, r1.mask):      # same decision from double scores: compare everything
+            np.testing.assert_array_equal(G.to_np(g.buf.perm)[:R], r1.perm)
+            np.testing.assert_array_equal(G.to_np(g.buf.inv).reshape(T, k), r1.inv)
+            G.assert_close_storage(y1, r1.y, "bf16", f"step1 y {pol}")
+            G.assert_close_storage(G.to_np(g.buf.H_cache).reshape(T * k, d), H.reshape(T * k, d), "bf16", "cache")
+            np.testing.assert_allclose(G.to_np(g.buf.S_cache), S, rtol=5e-5)
+        else:
+            assert pol.kind in (B.REFRESH_FRACTION_TOKEN, B.REFRESH_FRACTION_PAIR)
+            assert (m_gpu != r1.mask).sum() <= 2 * k, "float and double scores disagree on more than one swap"
+        # untouched cache entries are unchanged bit for bit
+        keep = m_gpu == 0
+        np.testing.assert_array_equal(G.to_np(g.buf.H_cache)[keep], Hc0[keep])
+        np.testing.assert_array_equal(G.to_np(g.buf.S_cache)[keep], Sc0[keep])
+        rel = np.linalg.norm(r1.y - sync1.y) / np.linalg.norm(sync1.y)
+        say(f"  {pol}: R={R}, rel-L2 of the approximation vs the synchronous step = {rel:.4f}")
+        if pol.kind == B.REFRESH_NONE:
+            np.testing.assert_array_equal(y1, y0)            # fraction 0: the cache, bit for bit
+        if pol.kind == B.REFRESH_FRACTION_TOKEN and pol.n_units == T:
+            y_sync = G.to_np(g.forward(None, x=x1_dev))       # fraction 1: the synchronous layer, bit for bit
+            np.testing.assert_array_equal(y1, y_sync)
+
+
+def test_conditional_refresh_config4_full_size_sampled():
+    li, x1, z1 = run_two_steps(WL.CONFIGS[4].T)
+    c, k, T = li.cfg, li.cfg.k, li.cfg.T
+    g = G.GpuLayer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, k, "bf16", with_cache=True)
+    x1_dev = G.to_dev(x1, "bf16")
+    st0 = oracle_index_stages(li, k)
+    r = np.random.Generator(np.random.PCG64(4))
+    for f in (0.5, 0.25, 0.75, 1.0):
+        n_units = int(np.floor(f * T + 0.5))
+        g.forward(B.Policy(B.REFRESH_ALL))
+        if f == 0.5:
+            sampled_layer_check(g, st0, li, k, "cfg4 step t-1", n_rows=32, n_tok=32)
+        Hc0 = G.to_np(g.buf.H_cache).copy()
+        Sc0 = G.to_np(g.buf.S_cache).copy()
+        y1 = G.to_np(g.forward(B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=n_units), x=x1_dev))
+        # integer stages on the GPU's float scores
+        s_gpu = G.to_np(g.buf.scores).astype(np.float64)
+        idx_gpu = G.to_np(g.buf.expert_idx)
+        np.testing.assert_array_equal(idx_gpu, O.topk(z1, k))
+        mask, R = O.refresh_mask(s_gpu, O.REFRESH_FRACTION_TOKEN, n_units=n_units)
+        np.testing.assert_array_equal(G.to_np(g.buf.mask), mask)
+        assert int(g.buf.n_refresh.item()) == R == n_units * k
+        counts, offsets, perm, inv = O.dispatch(idx_gpu, mask, c.E)
+        np.testing.assert_array_equal(G.to_np(g.buf.counts), counts)
+        np.testing.assert_array_equal(G.to_np(g.buf.perm)[:R], perm)
+        np.testing.assert_array_equal(G.to_np(g.buf.inv).reshape(T, k), inv)
+        # sampled tokens, refreshed and reused alike
+        toks = np.sort(r.choice(T, size=48, replace=False)).astype(np.int32)
+        rows = inv[toks].reshape(-1)
+        rows = np.unique(rows[rows >= 0]).astype(np.int32)
+        xp = G.to_np(g.buf.x_packed)[:R]
+        np.testing.assert_array_equal(xp, x1[perm // k])
+        h_ref = O.expert_ffn(xp, offsets, np.arange(c.E), li.W1, None, li.W2, None, rows_sel=rows)
+        G.assert_close_storage(G.to_np(g.buf.h_packed)[rows], h_ref, "bf16", f"cfg4 f={f} h rows")
+        h_sparse = np.zeros((max(R, 1), c.d)); h_sparse[rows] = h_ref
+        H64, S64 = Hc0.astype(np.float64), Sc0.astype(np.float64)
+        y_ref = O.combine(h_sparse, inv, s_gpu, mask, H64, S64, False, tokens_sel=toks)
+        G.assert_close_storage(y1[toks], y_ref, "bf16", f"cfg4 f={f} y tokens")
+        keep = mask == 0
+        np.testing.assert_array_equal(G.to_np(g.buf.H_cache)[keep], Hc0[keep])
+        say(f"  cfg4 f={f}: R={R}")
+
+
+# ----------------------------------------------------------------------------- expert-parallel shard (config 5)
+def test_ep_shard_config5_receive_side_sampled():
+    ep = WL.make_ep_shard()
+    c = ep.cfg
+    rows, E_loc, W = ep.x_recv.shape[0], 4, 4
+    say(f"config 5 receive side: rows={rows} recv_counts=\n{ep.recv_counts}")
+    ctx = B.Context(rows, c.d, c.F, E_loc, 1, "bf16")
+    seg_offsets = torch.empty(W * E_loc + 1, dtype=torch.int32, device=G.DEV)
+    seg_expert = torch.empty(W * E_loc, dtype=torch.int32, device=G.DEV)
+    ctx.moe_ep_segments(G.i32_dev(ep.recv_counts), seg_offsets, seg_expert)
+    so_ref, se_ref = O.ep_segments(ep.recv_counts)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(G.to_np(seg_offsets), so_ref)
+    np.testing.assert_array_equal(G.to_np(seg_expert), se_ref)
+    h = torch.zeros((rows, c.d), dtype=torch.bfloat16, device=G.DEV)
+    ws = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=G.DEV)
+    ctx.moe_expert_ffn(G.to_dev(ep.x_recv, "bf16"), seg_offsets, seg_expert, rows, G.to_dev(ep.W1, "bf16"), None,
+                       G.to_dev(ep.W2, "bf16"), None, h, ws)
+    torch.cuda.synchronize()
+    r = np.random.Generator(np.random.PCG64(5))
+    edge = np.unique(np.concatenate([so_ref[:-1], so_ref[1:] - 1]))
+    sel = np.unique(np.concatenate([edge, r.choice(rows, size=24, replace=False)])).astype(np.int32)
+    h_ref = O.expert_ffn(ep.x_recv, so_ref, se_ref, ep.W1, None, ep.W2, None, rows_sel=sel)
+    G.assert_close_storage(G.to_np(h)[sel], h_ref, "bf16", "cfg5 h rows")
+    load = ep.recv_counts.sum(axis=0)
+    say(f"  rows per local expert {load.tolist()}")
+
+
+def test_ep_shard_config5_source_side_gate_and_dispatch():
+    li, z = G.pick_layer(5, with_experts=False)
+    c = li.cfg
+    say(f"config 5 source side seed {li.seed}")
+    ctx = B.Context(c.T, c.d, c.F, c.E, c.k, "bf16")
+    buf = B.LayerBuffers(ctx, G.DEV, workspace=torch.empty(4096, dtype=torch.uint8, device=G.DEV))
+    x = G.to_dev(li.x, "bf16")
+    ctx.moe_gate(x, G.to_dev(li.Wg, "bf16"), G.f32_dev(li.bg), buf.scores, buf.expert_idx)
+    ctx.moe_dispatch(x, buf.expert_idx, None, buf.x_packed, buf.counts, buf.offsets, buf.perm, buf.inv, buf.workspace)
+    torch.cuda.synchronize()
+    idx = O.topk(z, c.k)
+    counts, offsets, perm, inv = O.dispatch(idx, None, c.E)
+    np.testing.assert_array_equal(G.to_np(buf.expert_idx), idx)
+    np.testing.assert_array_equal(G.to_np(buf.counts), counts)
+    np.testing.assert_array_equal(G.to_np(buf.perm), perm)
+    np.testing.assert_array_equal(G.to_np(buf.x_packed), li.x[perm // c.k])
+    send_counts = counts.reshape(c.ep_world, c.E // c.ep_world)      # [destination rank][local expert]
+    say(f"  send counts per destination rank {send_counts.sum(axis=1).tolist()}, "
+        f"hottest expert / mean = {counts.max() / counts.mean():.2f}")
+    assert counts.max() / counts.mean() > 3.0                          # Zipf-skewed load
+    # destination rank r's slice of the send buffer is contiguous
+    for rnk in range(c.ep_world):
+        lo, hi = offsets[rnk * 4], offsets[(rnk + 1) * 4]
+        assert ((idx.reshape(-1)[perm[lo:hi]] // 4) == rnk).all()
