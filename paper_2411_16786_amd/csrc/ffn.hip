@@ -15,42 +15,10 @@
 // MFMAs.  LDS rows are 128 bytes; the 16-byte chunk index is XOR-swizzled with row bits so that
 // the fragment reads (32 consecutive rows, same chunk) and the tile stores spread over all banks.
 #include "common.hpp"
+#include "ffn_mfma.hpp"
 #include "kernels.hpp"
 
 namespace dicemoe {
-
-typedef __bf16 bf16x8_v __attribute__((ext_vector_type(8)));
-typedef float f32x16_v __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ float gelu_erf(float u) {
-    return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
-}
-
-// Walk the segment table: which segment and which rows does row tile `tile` cover?
-__device__ __forceinline__ bool find_row_tile(const int32_t* __restrict__ seg_offsets, int n_seg, int BM, int tile,
-                                              int& seg, int& row0, int& row_end)
-{
-    int begin = seg_offsets[0];
-    for (int g = 0; g < n_seg; ++g) {
-        const int end = seg_offsets[g + 1];
-        const int cnt = end - begin;
-        const int nt = (cnt + BM - 1) / BM;
-        if (tile < nt) {
-            seg = g;
-            row0 = begin + tile * BM;
-            row_end = end;
-            return true;
-        }
-        tile -= nt;
-        begin = end;
-    }
-    return false;
-}
-
-// swizzle of the 16-byte chunk index inside a 128-byte LDS row (8 chunks per row)
-__device__ __forceinline__ int swz8(int row) {
-    return ((row >> 1) & 3) | ((((row) & 1) ^ ((row >> 3) & 1)) << 2);
-}
 
 template <int BM, int BN, bool GELU>
 __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
@@ -65,8 +33,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __rest
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_PASSES = BM / 32;   // 256 threads cover 32 rows x 8 chunks per pass
     constexpr int B_PASSES = BN / 32;
-    __shared__ uint4 As[BM * CH];
-    __shared__ uint4 Bs[BN * CH];
+    __shared__ u32x4_v As[BM * CH];
+    __shared__ u32x4_v Bs[BN * CH];
 
     const int tile_m = blockIdx.x / n_tiles_n;
     const int tile_n = blockIdx.x % n_tiles_n;
@@ -84,21 +52,21 @@ __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __rest
     // global -> register staging: thread covers chunk (tid % 8) of rows (tid / 8) + 32*pass
     const int ld_chunk = tid & 7;
     const int ld_row = tid >> 3;
-    const uint4* a_src[A_PASSES];
-    const uint4* b_src[B_PASSES];
+    const u32x4_v* a_src[A_PASSES];
+    const u32x4_v* b_src[B_PASSES];
 #pragma unroll
     for (int p = 0; p < A_PASSES; ++p) {
         int r = row0 + ld_row + 32 * p;
         if (r >= row_end) r = row_end - 1;                    // clamp: tail rows repeat the last row
-        a_src[p] = reinterpret_cast<const uint4*>(A + static_cast<size_t>(r) * K) + ld_chunk;
+        a_src[p] = reinterpret_cast<const u32x4_v*>(A + static_cast<size_t>(r) * K) + ld_chunk;
     }
 #pragma unroll
     for (int p = 0; p < B_PASSES; ++p) {
         int n = n0 + ld_row + 32 * p;
         if (n >= N) n = N - 1;
-        b_src[p] = reinterpret_cast<const uint4*>(We + static_cast<size_t>(n) * K) + ld_chunk;
+        b_src[p] = reinterpret_cast<const u32x4_v*>(We + static_cast<size_t>(n) * K) + ld_chunk;
     }
-    uint4 a_reg[A_PASSES], b_reg[B_PASSES];
+    u32x4_v a_reg[A_PASSES], b_reg[B_PASSES];
 #pragma unroll
     for (int p = 0; p < A_PASSES; ++p) a_reg[p] = a_src[p][0];
 #pragma unroll
@@ -117,12 +85,12 @@ __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __rest
 #pragma unroll
         for (int p = 0; p < A_PASSES; ++p) {
             const int r = ld_row + 32 * p;
-            As[r * CH + (ld_chunk ^ swz8(r))] = a_reg[p];
+            As[r * CH + (ld_chunk ^ chunk_swizzle<8>(r))] = a_reg[p];
         }
 #pragma unroll
         for (int p = 0; p < B_PASSES; ++p) {
             const int r = ld_row + 32 * p;
-            Bs[r * CH + (ld_chunk ^ swz8(r))] = b_reg[p];
+            Bs[r * CH + (ld_chunk ^ chunk_swizzle<8>(r))] = b_reg[p];
         }
         __syncthreads();
         if (kt + 1 < nk) {
@@ -139,13 +107,13 @@ __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __rest
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int r = wm * WM + i * 32 + (lane & 31);
-                const uint4 v = As[r * CH + (chunk ^ swz8(r))];
+                const u32x4_v v = As[r * CH + (chunk ^ chunk_swizzle<8>(r))];
                 af[i] = *reinterpret_cast<const bf16x8_v*>(&v);
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int r = wn * WN + j * 32 + (lane & 31);
-                const uint4 v = Bs[r * CH + (chunk ^ swz8(r))];
+                const u32x4_v v = Bs[r * CH + (chunk ^ chunk_swizzle<8>(r))];
                 bfr[j] = *reinterpret_cast<const bf16x8_v*>(&v);
             }
 #pragma unroll
