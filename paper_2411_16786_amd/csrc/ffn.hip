@@ -20,12 +20,65 @@
 
 namespace dicemoe {
 
-template <int BM, int BN, bool GELU>
-__global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
-                                                            const float* __restrict__ bias, bf16_t* __restrict__ C,
-                                                            int N, int K, const int32_t* __restrict__ seg_offsets,
-                                                            const int32_t* __restrict__ seg_expert, int n_seg,
-                                                            int n_tiles_n)
+// Epilogue shared by the bf16 kernels ("C-shuffle").  The MFMAs are issued with the operands swapped
+// (W fragment as the row operand, activation fragment as the column operand), so accumulator element v
+// of lane l belongs to output row (l % 32) and output column 8*(v/4) + 4*(l/32) + v%4 of its 32x32
+// block: four consecutive columns per group of four registers.  Each wavefront adds the bias, applies
+// GELU, packs four bf16 (8 bytes) and parks one 32-row slab of its sub-tile in a private LDS region
+// with a padded pitch; it then reads the slab back row-contiguously, 16 bytes per lane, and stores
+// full 16-byte pieces (whole cache lines per row) to global memory.  Only rows are predicated.
+template <int TN, bool GELU>
+__device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* region, const float* __restrict__ bias_n,
+                                           bf16_t* __restrict__ C, int N, int row_first, int row_end, int col_first,
+                                           int lane)
+{
+    constexpr int WN = TN * 32;
+    constexpr int PITCH = WN * 2 + 16;            // bytes; keeps 16-byte alignment, staggers banks
+    constexpr int CPR = WN / 8;                   // 16-byte chunks per slab row
+    const int m_local = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int nl = j * 32 + 8 * g + 4 * h;
+            float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
+            if (bias_n) {
+                const float4 bb = *reinterpret_cast<const float4*>(bias_n + nl);
+                b0 = bb.x; b1 = bb.y; b2 = bb.z; b3 = bb.w;
+            }
+            float v0 = half[j][4 * g] + b0, v1 = half[j][4 * g + 1] + b1;
+            float v2 = half[j][4 * g + 2] + b2, v3 = half[j][4 * g + 3] + b3;
+            if (GELU) { v0 = gelu_erf(v0); v1 = gelu_erf(v1); v2 = gelu_erf(v2); v3 = gelu_erf(v3); }
+            uint2 packed = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+            *reinterpret_cast<uint2*>(region + m_local * PITCH + nl * 2) = packed;
+        }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int p = 0; p < (32 * CPR + 63) / 64; ++p) {
+        const int idx = lane + 64 * p;
+        const int row = idx / CPR, chunk = idx % CPR;
+        if (idx < 32 * CPR) {
+            const u32x4_v v = *reinterpret_cast<const u32x4_v*>(region + row * PITCH + chunk * 16);
+            const int r = row_first + row;
+            const int n = col_first + chunk * 8;
+            if (r < row_end && n < N) *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(r) * N + n) = v;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Register-staged kernel: A and W tiles of depth 64 go global -> registers -> LDS (one LDS buffer, the
+// next tile's global loads are in flight during the MFMAs), so a workgroup needs only (BM+BN)*128
+// bytes of LDS and two or three workgroups share a compute unit and hide each other's barriers,
+// LDS stores and epilogues.
+template <int BM, int BN, int OCC, bool GELU>
+__global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* __restrict__ A,
+                                                                 const bf16_t* __restrict__ W,
+                                                                 const float* __restrict__ bias,
+                                                                 bf16_t* __restrict__ C, int N, int K,
+                                                                 const int32_t* __restrict__ seg_offsets,
+                                                                 const int32_t* __restrict__ seg_expert, int n_seg,
+                                                                 int n_tiles_n, int m_tiles_max)
 {
     constexpr int BK = 64;
     constexpr int CH = BK / 8;          // 16-byte chunks per tile row
@@ -33,11 +86,23 @@ __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __rest
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_PASSES = BM / 32;   // 256 threads cover 32 rows x 8 chunks per pass
     constexpr int B_PASSES = BN / 32;
-    __shared__ u32x4_v As[BM * CH];
-    __shared__ u32x4_v Bs[BN * CH];
+    constexpr int SLAB = 32 * (WN * 2 + 16);
+    static_assert(4 * SLAB <= (BM + BN) * BK * 2, "epilogue slabs must fit in the tile buffer");
+    __shared__ __attribute__((aligned(16))) char lds[(BM + BN) * BK * 2];
+    u32x4_v* As = reinterpret_cast<u32x4_v*>(lds);
+    u32x4_v* Bs = As + BM * CH;
 
-    const int tile_m = blockIdx.x / n_tiles_n;
-    const int tile_n = blockIdx.x % n_tiles_n;
+    // bands of 8 row tiles, row tile fastest: neighbouring workgroups share W row tiles
+    constexpr int GROUP_M = 8;
+    const int t = blockIdx.x;
+    const int band = t / (GROUP_M * n_tiles_n);
+    const int in_band = t % (GROUP_M * n_tiles_n);
+    const int left = m_tiles_max - band * GROUP_M;
+    const int rows_here = left < GROUP_M ? left : GROUP_M;
+    if (rows_here <= 0) return;
+    const int tile_m = band * GROUP_M + in_band % rows_here;
+    const int tile_n = in_band / rows_here;
+    if (tile_n >= n_tiles_n) return;
     int seg, row0, row_end;
     if (!find_row_tile(seg_offsets, n_seg, BM, tile_m, seg, row0, row_end)) return;
     const int e = seg_expert[seg];
@@ -71,6 +136,17 @@ __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __rest
     for (int p = 0; p < A_PASSES; ++p) a_reg[p] = a_src[p][0];
 #pragma unroll
     for (int p = 0; p < B_PASSES; ++p) b_reg[p] = b_src[p][0];
+    const int st_off = ld_row * CH + (ld_chunk ^ chunk_swizzle<8>(ld_row));   // + 32 rows per pass: same swizzle
+
+    // fragment read offsets: 32-row blocks sit 32*128 bytes apart, k-slices differ in chunk bits only
+    int a_off[BK / 16], b_off[BK / 16];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+        const int chunk = kk * 2 + (lane >> 5);
+        const int ra = wm * WM + (lane & 31), rb = wn * WN + (lane & 31);
+        a_off[kk] = ra * CH + (chunk ^ chunk_swizzle<8>(ra));
+        b_off[kk] = rb * CH + (chunk ^ chunk_swizzle<8>(rb));
+    }
 
     f32x16_v acc[TM][TN];
 #pragma unroll
@@ -83,15 +159,9 @@ __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __rest
     const int nk = K / BK;
     for (int kt = 0; kt < nk; ++kt) {
 #pragma unroll
-        for (int p = 0; p < A_PASSES; ++p) {
-            const int r = ld_row + 32 * p;
-            As[r * CH + (ld_chunk ^ chunk_swizzle<8>(r))] = a_reg[p];
-        }
+        for (int p = 0; p < A_PASSES; ++p) As[st_off + p * 32 * CH] = a_reg[p];
 #pragma unroll
-        for (int p = 0; p < B_PASSES; ++p) {
-            const int r = ld_row + 32 * p;
-            Bs[r * CH + (ld_chunk ^ chunk_swizzle<8>(r))] = b_reg[p];
-        }
+        for (int p = 0; p < B_PASSES; ++p) Bs[st_off + p * 32 * CH] = b_reg[p];
         __syncthreads();
         if (kt + 1 < nk) {
             const int koff = (kt + 1) * CH;
@@ -102,48 +172,33 @@ __global__ __launch_bounds__(256) void ffn_gemm_bf16_kernel(const bf16_t* __rest
         }
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            const int chunk = kk * 2 + (lane >> 5);
             bf16x8_v af[TM], bfr[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                const int r = wm * WM + i * 32 + (lane & 31);
-                const u32x4_v v = As[r * CH + (chunk ^ chunk_swizzle<8>(r))];
+                const u32x4_v v = As[a_off[kk] + i * 32 * CH];
                 af[i] = *reinterpret_cast<const bf16x8_v*>(&v);
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int r = wn * WN + j * 32 + (lane & 31);
-                const u32x4_v v = Bs[r * CH + (chunk ^ chunk_swizzle<8>(r))];
+                const u32x4_v v = Bs[b_off[kk] + j * 32 * CH];
                 bfr[j] = *reinterpret_cast<const bf16x8_v*>(&v);
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j)     // operands swapped: see store_slab
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
         __syncthreads();
     }
 
-    // epilogue: accumulator element v of lane l sits at column (l % 32), row 8*(v/4) + 4*(l/32) + v%4
+    // epilogue: the tile buffer is free (barrier above); every wavefront uses its own slab region
+    char* region = lds + wave * SLAB;
+    const int col_first = n0 + wn * WN;
+    const float* bias_n = bias ? bias + static_cast<size_t>(e) * N + col_first : nullptr;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * WN + j * 32 + (lane & 31);
-        if (n >= N) continue;
-        const float bv = bias ? bias[static_cast<size_t>(e) * N + n] : 0.f;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = row0 + wm * WM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (r < row_end) {
-                    float val = acc[i][j][v] + bv;
-                    if (GELU) val = gelu_erf(val);
-                    C[static_cast<size_t>(r) * N + n] = float_to_bf16(val);
-                }
-            }
-        }
-    }
+    for (int i = 0; i < TM; ++i)
+        store_slab<TN, GELU>(acc[i], region, bias_n, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
 }
 
 // float path (small workloads): 64x64 tile, depth 16, each thread a 4x4 block, plain FMAs in a
@@ -215,16 +270,17 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
     }
 }
 
-template <int BM, int BN, bool GELU>
+template <int BM, int BN, int OCC, bool GELU>
 static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                    const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
                                    hipStream_t stream)
 {
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
-    hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, GELU>), dim3(static_cast<unsigned>(m_tiles) * n_tiles_n), dim3(256),
-                       0, stream, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias,
-                       static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n);
+    const int bands = (m_tiles + 7) / 8;
+    hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, OCC, GELU>), dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n),
+                       dim3(256), 0, stream, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias,
+                       static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles);
     return hipGetLastError();
 }
 
@@ -249,10 +305,10 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_packed, const int32_t* seg
     if (max_rows == 0) return hipSuccess;
     hipError_t err;
     if (bf16) {
-        err = launch_gemm_bf16<128, 128, true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg,
+        err = launch_gemm_bf16<128, 128, 3, true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg,
                                                max_rows, stream);
         if (err != hipSuccess) return err;
-        return launch_gemm_bf16<128, 128, false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg,
+        return launch_gemm_bf16<128, 128, 3, false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg,
                                                  max_rows, stream);
     }
     err = launch_gemm_f32<true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream);

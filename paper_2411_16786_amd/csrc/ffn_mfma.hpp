@@ -22,6 +22,7 @@ namespace dicemoe {
 
 typedef __bf16 bf16x8_v __attribute__((ext_vector_type(8)));
 typedef float f32x16_v __attribute__((ext_vector_type(16)));
+typedef float f32x4_v __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_v __attribute__((ext_vector_type(4)));   // 16 bytes in four VGPRs
 
 #define DICEMOE_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
