@@ -10,6 +10,9 @@ constexpr int kWave = 64;
 constexpr int kMaxExperts = 64;
 
 typedef uint16_t bf16_t;  // raw bf16 bit pattern
+// 16 bytes in four VGPRs.  Arrays of this native vector type stay in registers, whereas arrays of
+// HIP's uint4 struct tend to be placed in scratch memory.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float bf16_to_float(bf16_t v) {
     return __uint_as_float(static_cast<uint32_t>(v) << 16);
@@ -30,6 +33,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 template <typename T> struct Store;
 template <> struct Store<float> {
     static constexpr int kVec = 4;
+    __device__ static __forceinline__ void unpack(const u32x4_t& v, float* f) {
+        f[0] = __uint_as_float(v[0]); f[1] = __uint_as_float(v[1]);
+        f[2] = __uint_as_float(v[2]); f[3] = __uint_as_float(v[3]);
+    }
     __device__ static __forceinline__ void unpack(const uint4& v, float* f) {
         f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
         f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
@@ -40,6 +47,12 @@ template <> struct Store<float> {
 };
 template <> struct Store<bf16_t> {
     static constexpr int kVec = 8;
+    __device__ static __forceinline__ void unpack(const u32x4_t& v, float* f) {
+        f[0] = __uint_as_float(v[0] << 16); f[1] = __uint_as_float(v[0] & 0xFFFF0000u);
+        f[2] = __uint_as_float(v[1] << 16); f[3] = __uint_as_float(v[1] & 0xFFFF0000u);
+        f[4] = __uint_as_float(v[2] << 16); f[5] = __uint_as_float(v[2] & 0xFFFF0000u);
+        f[6] = __uint_as_float(v[3] << 16); f[7] = __uint_as_float(v[3] & 0xFFFF0000u);
+    }
     __device__ static __forceinline__ void unpack(const uint4& v, float* f) {
         f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
         f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);

@@ -20,6 +20,13 @@ namespace dicemoe {
 constexpr int kIdxThreads = 1024;
 constexpr int kIdxWaves = kIdxThreads / kWave;
 
+// order this wavefront's LDS accesses: reads before the point complete before writes after it
+// are issued, and the compiler keeps them on their side
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // lanes of this wave that are live and hold the same expert id as the calling lane
 __device__ __forceinline__ uint64_t same_expert_peers(bool live, int e) {
     uint64_t peers = __ballot(live);
@@ -32,6 +39,37 @@ __device__ __forceinline__ uint64_t same_expert_peers(bool live, int e) {
     return peers;
 }
 
+constexpr int kChunk = 8;
+
+// Expert ids of one chunk of this wave's pairs, -1 where the pair is past the range, not refreshed
+// or carries a bad id.  The loads are unconditional (index clamped into the range) so that the
+// whole chunk is in flight at once.
+__device__ __forceinline__ void load_chunk(const int32_t* __restrict__ expert_idx, const uint8_t* __restrict__ mask,
+                                           int c0, int lane, int hi, int E, int (&ev)[kChunk]) {
+    uint8_t mv[kChunk];
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+        const int p = c0 + u * kWave + lane;
+        ev[u] = expert_idx[p < hi ? p : hi - 1];
+    }
+    if (mask != nullptr) {
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            const int p = c0 + u * kWave + lane;
+            mv[u] = mask[p < hi ? p : hi - 1];
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) mv[u] = 1;
+    }
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+        const int p = c0 + u * kWave + lane;
+        const bool ok = p < hi && mv[u] != 0 && static_cast<unsigned>(ev[u]) < static_cast<unsigned>(E);
+        ev[u] = ok ? ev[u] : -1;
+    }
+}
+
 __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32_t* __restrict__ expert_idx,
                                                                     const uint8_t* __restrict__ mask, int N, int E,
                                                                     int32_t* __restrict__ counts,
@@ -39,7 +77,7 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
                                                                     int32_t* __restrict__ perm,
                                                                     int32_t* __restrict__ inv)
 {
-    __shared__ volatile int wave_run[kIdxWaves][kMaxExperts];  // counts, then running bases
+    __shared__ int wave_run[kIdxWaves][kMaxExperts];  // counts, then running bases
     __shared__ int s_cnt[kMaxExperts];
     __shared__ int s_off[kMaxExperts + 1];
     const int tid = threadIdx.x;
@@ -52,15 +90,20 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
     wave_run[tid / kMaxExperts][tid % kMaxExperts] = 0;   // 1024 threads cover the 16 x 64 table
     __syncthreads();
 
+    // Both phases walk the range in chunks of kChunk wave-wide steps: all loads of a chunk are
+    // issued first (they are independent), then the steps are processed from registers in order.
     // phase A: per-wave, per-expert counts of refreshed pairs
-    for (int p0 = lo; p0 < hi; p0 += kWave) {
-        const int p = p0 + lane;
-        bool live = p < hi && (mask == nullptr || mask[p] != 0);
-        int e = live ? expert_idx[p] : 0;
-        if (static_cast<unsigned>(e) >= static_cast<unsigned>(E)) { live = false; e = 0; }  // ignore a bad id
-        const uint64_t peers = same_expert_peers(live, e);
-        if (live && (peers & lanemask_lt()) == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
-        __builtin_amdgcn_wave_barrier();
+    for (int c0 = lo; c0 < hi; c0 += kWave * kChunk) {
+        int ev[kChunk];
+        load_chunk(expert_idx, mask, c0, lane, hi, E, ev);
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            const bool live = ev[u] >= 0;
+            const int e = live ? ev[u] : 0;
+            const uint64_t peers = same_expert_peers(live, e);
+            if (live && (peers & lanemask_lt()) == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
+            wave_sync();
+        }
     }
     __syncthreads();
 
@@ -86,21 +129,24 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
     const int R = s_off[E];
 
     // phase B: final positions
-    for (int p0 = lo; p0 < hi; p0 += kWave) {
-        const int p = p0 + lane;
-        const bool in_range = p < hi;
-        bool live = in_range && (mask == nullptr || mask[p] != 0);
-        int e = live ? expert_idx[p] : 0;
-        if (static_cast<unsigned>(e) >= static_cast<unsigned>(E)) { live = false; e = 0; }
-        const uint64_t peers = same_expert_peers(live, e);
-        const int before = __popcll(peers & lanemask_lt());
-        int r = -1;
-        if (live) r = s_off[e] + wave_run[wave][e] + before;
-        __builtin_amdgcn_wave_barrier();
-        if (live && before == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
-        __builtin_amdgcn_wave_barrier();
-        if (live) perm[r] = p;
-        if (in_range) inv[p] = r;
+    for (int c0 = lo; c0 < hi; c0 += kWave * kChunk) {
+        int ev[kChunk];
+        load_chunk(expert_idx, mask, c0, lane, hi, E, ev);
+#pragma unroll
+        for (int u = 0; u < kChunk; ++u) {
+            const int p = c0 + u * kWave + lane;
+            const bool live = ev[u] >= 0;
+            const int e = live ? ev[u] : 0;
+            const uint64_t peers = same_expert_peers(live, e);
+            const int before = __popcll(peers & lanemask_lt());
+            int r = -1;
+            if (live) r = s_off[e] + wave_run[wave][e] + before;
+            wave_sync();
+            if (live && before == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
+            wave_sync();
+            if (live) perm[r] = p;
+            if (p < hi) inv[p] = r;
+        }
     }
     for (int r = R + tid; r < N; r += kIdxThreads) perm[r] = -1;
 }
