@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=None, help="override the 28 layers (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy five times (reference for scaling HBM counters)")
     ap.add_argument("--eager", action="store_true", help="launch from Python every step instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -63,7 +65,7 @@ def main():
         buf = B.LayerBuffers(ctx, dev, workspace=workspace)
         layers.append(dict(x=up(li.x), Wg=up(li.Wg), bg=torch.from_numpy(li.bg).to(dev), W1=up(li.W1),
                            W2=up(li.W2), buf=buf))
-    layer0 = host_layers[0]
+    cpu_layers = host_layers[:4]          # kept on the host for the oracle's timed sample
     del host_layers
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
@@ -143,34 +145,53 @@ def main():
         stages[s].update({"algorithmic_bytes": nbytes, "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)})
     stages["expert_ffn"].update({"flops": ffn_flops, "TFLOP/s": round(ffn_tflops, 1),
                                  "frac_mfma": round(ffn_tflops / PEAK_BF16_TFLOPS, 4)})
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "bench_xl28_hbm_traffic.txt")
+    if os.path.exists(tpath):          # rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this same command (not live)
+        for line in open(tpath):
+            if line.startswith("ffn_traffic_bytes_per_call:"):
+                traffic = int(line.split(":")[1].split()[0])
     roofline = {"kernel": "ffn_gemm_bf16 (GEMM1 + GEMM2 of one moe_expert_ffn call)", "bound": "mfma",
                 "achieved": round(ffn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ffn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None}
+                "frac": round(ffn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "traffic_note": "HBM-side bytes per moe_expert_ffn call from profiles/bench_xl28_hbm_traffic.txt"}
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- the CPU oracle on a bounded sample of the same workload (layer 0, first tokens)
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O
-        n_tok = 256
-        xs = layer0.x[:n_tok]
         t1 = time.perf_counter()
-        ref = O.moe_layer(xs, layer0.Wg, layer0.bg, layer0.W1, None, layer0.W2, None, k)
+        refs = [O.moe_layer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, k) for li in cpu_layers]
         cpu_s = time.perf_counter() - t1
-        # the same tokens through the HIP path, as a live parity check of the benchmarked code
-        L = layers[0]
-        ctx_s = B.Context(n_tok, d, F, E, k, "bf16")
-        buf_s = B.LayerBuffers(ctx_s, dev)
-        y = B.moe_layer_forward(ctx_s, buf_s, L["x"][:n_tok].contiguous(), L["Wg"], L["bg"], L["W1"], None,
-                                L["W2"], None)
-        torch.cuda.synchronize()
-        got = y.float().cpu().numpy()
-        rel = float(np.linalg.norm(got - ref.y) / np.linalg.norm(ref.y))
-        assert np.array_equal(buf_s.expert_idx.cpu().numpy(), ref.idx), "routing differs from the oracle"
-        assert rel <= 1e-2 and np.abs(got - ref.y).max() <= 2e-2, "bench output differs from the oracle"
-        cpu_baseline = {"value": round(n_tok / cpu_s, 2), "unit": "tokens/s (one MoE layer)",
+        # the same layers through the HIP path (the buffers still hold the last timed pass): a live
+        # parity check of exactly the code that was benchmarked
+        worst = 0.0
+        for L, ref in zip(layers, refs):
+            got = L["buf"].y.float().cpu().numpy()
+            # tokens whose k-th and (k+1)-th logits are closer than float accumulation resolves are
+            # left out of the comparison (none at the seeds in use; the guard keeps the check honest)
+            zs = -np.sort(-ref.z, axis=1)
+            safe = np.min(zs[:, :k] - zs[:, 1:k + 1], axis=1) > 1e-4
+            assert safe.mean() > 0.999
+            assert np.array_equal(L["buf"].expert_idx.cpu().numpy()[safe], ref.idx[safe]), "routing differs from the oracle"
+            if safe.all():
+                assert np.array_equal(L["buf"].perm.cpu().numpy(), ref.perm), "permutation differs from the oracle"
+            rel = float(np.linalg.norm(got[safe] - ref.y[safe]) / np.linalg.norm(ref.y[safe]))
+            assert rel <= 1e-2 and np.abs(got[safe] - ref.y[safe]).max() <= 2e-2, "bench output differs from the oracle"
+            worst = max(worst, rel)
+        n_lay = len(cpu_layers)
+        cpu_baseline = {"value": round(T * n_lay / cpu_s, 2), "unit": "tokens/s (token passes through one MoE layer)",
                         "cores": O.num_threads(), "kind": "oracle",
-                        "sample": f"first {n_tok} tokens of layer 0 through the whole layer, {cpu_s:.2f} s; "
-                                  f"HIP path on the same tokens: rel-L2 {rel:.2e} vs the oracle"}
+                        "sample": f"layers 0..{n_lay - 1} of the same workload, whole layers (T={T}), {cpu_s:.2f} s; "
+                                  f"HIP outputs of these layers vs the oracle: worst rel-L2 {worst:.2e}"}
 
     out = {
         "metric": "MoE-layer tokens/sec at DiT-MoE-XL shape",

@@ -71,7 +71,7 @@ __device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* reg
 // next tile's global loads are in flight during the MFMAs), so a workgroup needs only (BM+BN)*128
 // bytes of LDS and two or three workgroups share a compute unit and hide each other's barriers,
 // LDS stores and epilogues.
-template <int BM, int BN, int OCC, bool GELU>
+template <int BM, int BN, int OCC, bool XCD, bool PF, bool GELU>
 __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                  const bf16_t* __restrict__ W,
                                                                  const float* __restrict__ bias,
@@ -92,9 +92,12 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
     u32x4_v* As = reinterpret_cast<u32x4_v*>(lds);
     u32x4_v* Bs = As + BM * CH;
 
-    // bands of 8 row tiles, row tile fastest: neighbouring workgroups share W row tiles
+    // Tile sequence: bands of 8 row tiles, row tile fastest, so neighbours in the sequence share W
+    // row tiles and a band shares its A rows.  Workgroups are handed to the 8 XCDs round robin
+    // (blockIdx % 8); giving XCD x the x-th contiguous eighth of the sequence keeps each XCD's L2
+    // working on its own bands instead of every L2 fetching every tile.
     constexpr int GROUP_M = 8;
-    const int t = blockIdx.x;
+    const int t = XCD ? (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3) : blockIdx.x;
     const int band = t / (GROUP_M * n_tiles_n);
     const int in_band = t % (GROUP_M * n_tiles_n);
     const int left = m_tiles_max - band * GROUP_M;
@@ -170,27 +173,55 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
 #pragma unroll
             for (int p = 0; p < B_PASSES; ++p) b_reg[p] = b_src[p][koff];
         }
+        if (PF) {
+            // all fragments of the step first (one exposed LDS latency per step instead of four),
+            // then hand the buffer back, then the MFMAs: they overlap the next step's LDS stores
+            bf16x8_v af[BK / 16][TM], bfr[BK / 16][TN];
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8_v af[TM], bfr[TN];
+            for (int kk = 0; kk < BK / 16; ++kk) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const u32x4_v v = As[a_off[kk] + i * 32 * CH];
-                af[i] = *reinterpret_cast<const bf16x8_v*>(&v);
+                for (int i = 0; i < TM; ++i) {
+                    const u32x4_v v = As[a_off[kk] + i * 32 * CH];
+                    af[kk][i] = *reinterpret_cast<const bf16x8_v*>(&v);
+                }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const u32x4_v v = Bs[b_off[kk] + j * 32 * CH];
+                    bfr[kk][j] = *reinterpret_cast<const bf16x8_v*>(&v);
+                }
             }
+            __syncthreads();
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const u32x4_v v = Bs[b_off[kk] + j * 32 * CH];
-                bfr[j] = *reinterpret_cast<const bf16x8_v*>(&v);
+            for (int kk = 0; kk < BK / 16; ++kk)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                bf16x8_v af[TM], bfr[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const u32x4_v v = As[a_off[kk] + i * 32 * CH];
+                    af[i] = *reinterpret_cast<const bf16x8_v*>(&v);
+                }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const u32x4_v v = Bs[b_off[kk] + j * 32 * CH];
+                    bfr[j] = *reinterpret_cast<const bf16x8_v*>(&v);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)     // operands swapped: see store_slab
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
             }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)     // operands swapped: see store_slab
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+            __syncthreads();
         }
-        __syncthreads();
     }
+    if (PF) __syncthreads();                     // the slabs below reuse the tile buffer
 
     // epilogue: the tile buffer is free (barrier above); every wavefront uses its own slab region
     char* region = lds + wave * SLAB;
@@ -270,7 +301,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
     }
 }
 
-template <int BM, int BN, int OCC, bool GELU>
+template <int BM, int BN, int OCC, bool XCD, bool PF, bool GELU>
 static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                    const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
                                    hipStream_t stream)
@@ -278,7 +309,7 @@ static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bi
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
     const int bands = (m_tiles + 7) / 8;
-    hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, OCC, GELU>), dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n),
+    hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, OCC, XCD, PF, GELU>), dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n),
                        dim3(256), 0, stream, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias,
                        static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles);
     return hipGetLastError();
@@ -305,10 +336,10 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_packed, const int32_t* seg
     if (max_rows == 0) return hipSuccess;
     hipError_t err;
     if (bf16) {
-        err = launch_gemm_bf16<128, 128, 3, true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg,
+        err = launch_gemm_bf16<128, 128, 3, true, false, true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg,
                                                max_rows, stream);
         if (err != hipSuccess) return err;
-        return launch_gemm_bf16<128, 128, 3, false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg,
+        return launch_gemm_bf16<128, 128, 3, true, false, false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg,
                                                  max_rows, stream);
     }
     err = launch_gemm_f32<true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream);
