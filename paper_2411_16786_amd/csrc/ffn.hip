@@ -48,7 +48,7 @@ __device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* reg
             }
             float v0 = half[j][4 * g] + b0, v1 = half[j][4 * g + 1] + b1;
             float v2 = half[j][4 * g + 2] + b2, v3 = half[j][4 * g + 3] + b3;
-            if (GELU) { v0 = gelu_erf(v0); v1 = gelu_erf(v1); v2 = gelu_erf(v2); v3 = gelu_erf(v3); }
+            if (GELU) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
             uint2 packed = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
             *reinterpret_cast<uint2*>(region + m_local * PITCH + nl * 2) = packed;
         }

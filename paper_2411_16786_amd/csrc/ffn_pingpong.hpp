@@ -35,7 +35,7 @@ __device__ __forceinline__ int xcd_patch_position(int bid) {
     return (((slot >> 5) * 8 + xcd) << 5) + (slot & 31);
 }
 
-template <int BN, int GROUP_M, bool GELU>
+template <int BN, int GROUP_M, bool GELU, int DIAG = 0>
 __global__ __launch_bounds__(512, 2) void ffn_gemm_bf16_pingpong_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
@@ -166,6 +166,7 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_bf16_pingpong_kernel(
     // barrier kt: publishes step kt+1 (every wavefront has waited for its own DMA of that step; the
     // only younger loads are step kt+2's) and frees step kt's buffer for the DMA of step kt+3
     auto sync_and_refill = [&](int kt, int stage) {
+        if (DIAG & 2) { if (kt == 0) wait_vmcnt<0>(); block_barrier(); return; }   // timing study: no refill
         if (kt + 2 < nk) wait_vmcnt<QW>();
         else wait_vmcnt<0>();
         block_barrier();
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_bf16_pingpong_kernel(
 
     int stage = 0;
     for (int kt = 0; kt < nk; ++kt) {
-        read_fragments(stage);                   // group 0: after barrier kt-1; group 1: before barrier kt
+        if (!(DIAG & 4) || kt == 0) read_fragments((DIAG & 2) ? 0 : stage);   // group 0: after barrier kt-1; group 1: before barrier kt
         if (grp == 1) {
             wait_lgkm0();                        // reads complete before the buffer is handed back
             sync_and_refill(kt, stage);
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_bf16_pingpong_kernel(
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int r = row0 + wm * 64 + i * 32 + g * 8 + (lane >> 5) * 4 + u;
-                    if (r < row_end && n < N) {
+                    if (r < row_end && n < N && (!(DIAG & 1) || v[u] == 123456.789f)) {
                         float val = half[j][4 * g + u] + v[u] + bv;
                         if (GELU) val = gelu_erf(val);
                         C[static_cast<size_t>(r) * N + n] = float_to_bf16(val);
@@ -224,12 +225,12 @@ __global__ __launch_bounds__(512, 2) void ffn_gemm_bf16_pingpong_kernel(
     if (grp == 0) absorb_and_store(acc[0], 0); else absorb_and_store(acc[1], 1);
 }
 
-template <int BN, int GROUP_M, bool GELU>
+template <int BN, int GROUP_M, bool GELU, int DIAG = 0>
 static hipError_t launch_gemm_bf16_pingpong(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                             const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                             int max_rows, hipStream_t stream)
 {
-    auto kern = ffn_gemm_bf16_pingpong_kernel<BN, GROUP_M, GELU>;
+    auto kern = ffn_gemm_bf16_pingpong_kernel<BN, GROUP_M, GELU, DIAG>;
     constexpr int smem = 3 * (128 + BN) * 64 * 2;
     static bool configured = false;
     if (!configured) {
