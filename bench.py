@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy five times (reference for scaling HBM counters)")
+    ap.add_argument("--refresh-sweep", action="store_true",
+                    help="also time the 512px conditional-communication workload (T=8192) at refresh fractions "
+                         "25/50/75/100 %% and report it under 'conditional_refresh'")
     ap.add_argument("--eager", action="store_true", help="launch from Python every step instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -164,6 +167,35 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---- optional: Conditional Communication at the 512px shape (two consecutive diffusion steps)
+    cond = None
+    if args.refresh_sweep:
+        c4 = WL.CONFIGS[4]
+        li4 = WL.make_layer(4)
+        x_prev, x_next = up(li4.x), up(WL.next_step_x(4, li4.x))
+        ctx4 = B.Context(c4.T, c4.d, c4.F, c4.E, c4.k, "bf16")
+        buf4 = B.LayerBuffers(ctx4, dev, with_cache=True)
+        w4 = (up(li4.Wg), None, up(li4.W1), None, up(li4.W2), None)
+        cond = []
+        for frac in (1.0, 0.75, 0.5, 0.25):
+            n_units = int(frac * c4.T + 0.5)
+            pol = B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=n_units)
+            B.moe_layer_forward(ctx4, buf4, x_prev, *w4, policy=B.Policy(B.REFRESH_ALL))      # fills the cache
+            for _ in range(3):
+                B.moe_layer_forward(ctx4, buf4, x_next, *w4, policy=pol, max_rows=n_units * c4.k)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 20
+            e0.record()
+            for _ in range(reps):
+                B.moe_layer_forward(ctx4, buf4, x_next, *w4, policy=pol, max_rows=n_units * c4.k)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            cond.append({"refresh_fraction": frac, "policy": "FRACTION_TOKEN", "refreshed_pairs": n_units * c4.k,
+                         "ms_per_layer": round(ms, 4), "tokens_per_s": round(c4.T / (ms * 1e-3), 1),
+                         "ffn_flops_needed": 4.0 * n_units * c4.k * c4.d * c4.F})
+        del buf4, w4
+
     # ---- the CPU oracle on a bounded sample of the same workload (layer 0, first tokens)
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -208,6 +240,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "stages": stages,
+        "conditional_refresh": cond,
         "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))
