@@ -25,8 +25,14 @@ __device__ __forceinline__ bf16_t float_to_bf16(float f) {
     return static_cast<bf16_t>(u >> 16);
 }
 
+// two floats -> two bf16 in one register: the hardware conversion (v_cvt_pk_bf16_f32, round to
+// nearest even, the same rounding as float_to_bf16 for finite values)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return static_cast<uint32_t>(float_to_bf16(lo)) | (static_cast<uint32_t>(float_to_bf16(hi)) << 16);
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<const uint32_t*>(&r);
 }
 
 // storage-type traits: kVec elements fill 16 bytes

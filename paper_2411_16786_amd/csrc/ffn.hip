@@ -16,56 +16,10 @@
 // the fragment reads (32 consecutive rows, same chunk) and the tile stores spread over all banks.
 #include "common.hpp"
 #include "ffn_mfma.hpp"
+#include "ffn_wide.hpp"
 #include "kernels.hpp"
 
 namespace dicemoe {
-
-// Epilogue shared by the bf16 kernels ("C-shuffle").  The MFMAs are issued with the operands swapped
-// (W fragment as the row operand, activation fragment as the column operand), so accumulator element v
-// of lane l belongs to output row (l % 32) and output column 8*(v/4) + 4*(l/32) + v%4 of its 32x32
-// block: four consecutive columns per group of four registers.  Each wavefront adds the bias, applies
-// GELU, packs four bf16 (8 bytes) and parks one 32-row slab of its sub-tile in a private LDS region
-// with a padded pitch; it then reads the slab back row-contiguously, 16 bytes per lane, and stores
-// full 16-byte pieces (whole cache lines per row) to global memory.  Only rows are predicated.
-template <int TN, bool GELU>
-__device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* region, const float* __restrict__ bias_n,
-                                           bf16_t* __restrict__ C, int N, int row_first, int row_end, int col_first,
-                                           int lane)
-{
-    constexpr int WN = TN * 32;
-    constexpr int PITCH = WN * 2 + 16;            // bytes; keeps 16-byte alignment, staggers banks
-    constexpr int CPR = WN / 8;                   // 16-byte chunks per slab row
-    const int m_local = lane & 31, h = lane >> 5;
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int nl = j * 32 + 8 * g + 4 * h;
-            float b0 = 0.f, b1 = 0.f, b2 = 0.f, b3 = 0.f;
-            if (bias_n) {
-                const float4 bb = *reinterpret_cast<const float4*>(bias_n + nl);
-                b0 = bb.x; b1 = bb.y; b2 = bb.z; b3 = bb.w;
-            }
-            float v0 = half[j][4 * g] + b0, v1 = half[j][4 * g + 1] + b1;
-            float v2 = half[j][4 * g + 2] + b2, v3 = half[j][4 * g + 3] + b3;
-            if (GELU) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
-            uint2 packed = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
-            *reinterpret_cast<uint2*>(region + m_local * PITCH + nl * 2) = packed;
-        }
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int p = 0; p < (32 * CPR + 63) / 64; ++p) {
-        const int idx = lane + 64 * p;
-        const int row = idx / CPR, chunk = idx % CPR;
-        if (idx < 32 * CPR) {
-            const u32x4_v v = *reinterpret_cast<const u32x4_v*>(region + row * PITCH + chunk * 16);
-            const int r = row_first + row;
-            const int n = col_first + chunk * 8;
-            if (r < row_end && n < N) *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(r) * N + n) = v;
-        }
-    }
-    __builtin_amdgcn_wave_barrier();
-}
 
 // Register-staged kernel: A and W tiles of depth 64 go global -> registers -> LDS (one LDS buffer, the
 // next tile's global loads are in flight during the MFMAs), so a workgroup needs only (BM+BN)*128
@@ -86,8 +40,8 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_PASSES = BM / 32;   // 256 threads cover 32 rows x 8 chunks per pass
     constexpr int B_PASSES = BN / 32;
-    constexpr int SLAB = 32 * (WN * 2 + 16);
-    static_assert(4 * SLAB <= (BM + BN) * BK * 2, "epilogue slabs must fit in the tile buffer");
+    constexpr int REGION = epilogue_region_bytes<TN>();
+    static_assert(4 * REGION <= (BM + BN) * BK * 2, "epilogue slabs must fit in the tile buffer");
     __shared__ __attribute__((aligned(16))) char lds[(BM + BN) * BK * 2];
     u32x4_v* As = reinterpret_cast<u32x4_v*>(lds);
     u32x4_v* Bs = As + BM * CH;
@@ -116,6 +70,11 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+
+    // bias of this wavefront's columns, fetched now and used in the epilogue
+    const int col_first = n0 + wn * WN;
+    float bias_reg[(WN + 63) / 64];
+    load_bias_columns<WN>(bias ? bias + static_cast<size_t>(e) * N + col_first : nullptr, N - col_first, lane, bias_reg);
 
     // global -> register staging: thread covers chunk (tid % 8) of rows (tid / 8) + 32*pass
     const int ld_chunk = tid & 7;
@@ -224,12 +183,12 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
     if (PF) __syncthreads();                     // the slabs below reuse the tile buffer
 
     // epilogue: the tile buffer is free (barrier above); every wavefront uses its own slab region
-    char* region = lds + wave * SLAB;
-    const int col_first = n0 + wn * WN;
-    const float* bias_n = bias ? bias + static_cast<size_t>(e) * N + col_first : nullptr;
+    char* region = lds + wave * REGION;
+    float* bias_lds = reinterpret_cast<float*>(region + slab_bytes<TN>());
+    stage_bias<WN>(bias_reg, bias_lds, lane);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-        store_slab<TN, GELU>(acc[i], region, bias_n, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
+        store_slab<TN, GELU>(acc[i], region, bias_lds, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
 }
 
 // float path (small workloads): 64x64 tile, depth 16, each thread a 4x4 block, plain FMAs in a
@@ -328,6 +287,32 @@ static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bia
     return hipGetLastError();
 }
 
+// Tile shape for one bf16 grouped GEMM.  The wide kernel fetches fewer bytes per flop and keeps the
+// matrix pipe fed from hand-scheduled wavefronts, and wins as soon as its tiles fill most of the chip:
+//   256 x 192 (one workgroup per compute unit) for the GEMM with the plain epilogue;
+//   128 x 192 (two workgroups per compute unit) for the GEMM whose epilogue evaluates GELU, so that one
+//   workgroup's MFMAs cover the other's epilogue arithmetic.
+// Small problems stay on the 128 x 128 kernel, three workgroups per compute unit: a wide-tile grid that
+// covers a fraction of the 256 compute units leaves the rest idle.
+template <bool GELU>
+static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const float* bias, void* C, int N, int K,
+                                        const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
+                                        int max_rows, hipStream_t stream)
+{
+    constexpr int kComputeUnits = 256;
+    // expected tiles: every segment ends in a partial row tile, half a tile on average
+    auto tiles = [&](int bm, int bn) {
+        const long long m_tiles = (static_cast<long long>(max_rows) + static_cast<long long>(n_seg) * bm / 2 + bm - 1) / bm;
+        return m_tiles * ((N + bn - 1) / bn);
+    };
+    const bool fits_192 = (N + 191) / 192 * 192 * 8 <= N * 9;          // at most 1/8 of the columns computed in vain
+    if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6)
+        return launch_gemm_bf16_wide<4, 3, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+    if (fits_192 && tiles(128, 192) * 10 >= 2 * kComputeUnits * 6)
+        return launch_gemm_bf16_wide<2, 3, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+    return launch_gemm_bf16<128, 128, 3, true, false, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+}
+
 hipError_t launch_expert_ffn(bool bf16, const void* x_packed, const int32_t* seg_offsets,
                              const int32_t* seg_expert, int n_seg, int max_rows, int d, int F, const void* W1,
                              const float* b1, const void* W2, const float* b2, void* h_packed, void* hidden,
@@ -336,11 +321,9 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_packed, const int32_t* seg
     if (max_rows == 0) return hipSuccess;
     hipError_t err;
     if (bf16) {
-        err = launch_gemm_bf16<128, 128, 3, true, false, true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg,
-                                               max_rows, stream);
+        err = launch_gemm_bf16_auto<true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream);
         if (err != hipSuccess) return err;
-        return launch_gemm_bf16<128, 128, 3, true, false, false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg,
-                                                 max_rows, stream);
+        return launch_gemm_bf16_auto<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream);
     }
     err = launch_gemm_f32<true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream);
     if (err != hipSuccess) return err;

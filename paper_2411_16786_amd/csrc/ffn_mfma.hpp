@@ -32,23 +32,24 @@ __device__ __forceinline__ float gelu_erf(float u) {
     return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f));
 }
 
-// GELU for the bf16 path: the same erf form, with erf from the rational-exponential formula of
-// Abramowitz & Stegun 7.1.26, erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1/(1 + p x), whose
-// absolute error is below 1.5e-7 -- four orders of magnitude under the bf16 rounding (2^-9 relative)
-// that the result receives next.  One reciprocal, one exp2 and a dozen FMAs instead of the library
-// routine's branchy polynomial: the epilogue of the first GEMM evaluates it 4608 times per row.
+// GELU for the bf16 path, u Phi(u) with Phi the standard normal distribution function (the erf form,
+// not the tanh approximation), written as  gelu(u) = max(u, 0) - a Phi(-a),  a = |u|.
+// log2 Phi(-a) is smooth and nearly quadratic, so a degree-6 polynomial in a (weighted minimax fit on
+// [0, 6], coefficients from gelu_fit.py beside the package) followed by one exp2 reproduces a Phi(-a)
+// to 6e-8 absolute; beyond a = 6 the term is below 1e-8 and a is clamped.  In float arithmetic the
+// result is within 3e-7 of the exact GELU everywhere, four orders of magnitude under the bf16 rounding
+// (2^-9 relative) that it receives next.  Cost: one transcendental (exp2) and nine plain operations; the
+// epilogue of the first GEMM evaluates it 4608 times per row.
 __device__ __forceinline__ float gelu_erf_fast(float u) {
-    const float x = fabsf(u) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-    float poly = fmaf(1.061405429f, t, -1.453152027f);
-    poly = fmaf(poly, t, 1.421413741f);
-    poly = fmaf(poly, t, -0.284496736f);
-    poly = fmaf(poly, t, 0.254829592f);
-    poly *= t;
-    const float ex = __builtin_amdgcn_exp2f(-1.4426950408889634f * x * x);
-    const float erf_abs = fmaf(-poly, ex, 1.0f);            // erf(|u| / sqrt 2)
-    const float half_u = 0.5f * u;
-    return fmaf(fabsf(half_u), erf_abs, half_u);             // u/2 + |u|/2 erf(|u|/sqrt2) = u/2 (1 + erf(u/sqrt2))
+    const float a = fminf(fabsf(u), 6.0f);
+    float p = fmaf(0x1.159ab2p-15f, a, -0x1.934b26p-11f);
+    p = fmaf(p, a, 0x1.08ca02p-7f);
+    p = fmaf(p, a, -0x1.b58d52p-5f);
+    p = fmaf(p, a, -0x1.d5c80ep-2f);
+    p = fmaf(p, a, -0x1.26b528p+0f);
+    p = fmaf(p, a, -0x1.ffff18p-1f);
+    const float tail = __builtin_amdgcn_exp2f(p);            // Phi(-a)
+    return fmaf(-a, tail, fmaxf(u, 0.0f));
 }
 
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt in bits 3:0 and 15:14; expcnt, lgkmcnt left open)
@@ -94,6 +95,80 @@ template <> __device__ __forceinline__ int chunk_swizzle<8>(int row) {
 }
 template <> __device__ __forceinline__ int chunk_swizzle<4>(int row) {
     return ((row >> 2) & 3) ^ (((row >> 1) & 1) << 1);
+}
+
+// Epilogue shared by the bf16 kernels ("C-shuffle").  The MFMAs are issued with the operands swapped
+// (W fragment as the row operand, activation fragment as the column operand), so accumulator element v
+// of lane l belongs to output row (l % 32) and output column 8*(v/4) + 4*(l/32) + v%4 of its 32x32
+// block: four consecutive columns per group of four registers.  Each wavefront adds the bias, applies
+// GELU, packs four bf16 (8 bytes) and parks one 32-row slab of its sub-tile in a private LDS region
+// with a padded pitch; it then reads the slab back row-contiguously, 16 bytes per lane, and stores
+// full 16-byte pieces (whole cache lines per row) to global memory.  Only rows are predicated.
+//
+// The bias of the wavefront's WN columns is fetched once, at kernel start, into WN/64 registers per
+// lane (load_bias_columns), long before it is needed; stage_bias parks it in LDS behind the slab and
+// the groups read their four values from there.  (Fetching it from global memory group by group put a
+// full memory round trip in front of every group.)
+template <int WN>
+__device__ __forceinline__ void load_bias_columns(const float* __restrict__ bias_n, int n_valid, int lane,
+                                                  float (&reg)[(WN + 63) / 64])
+{
+#pragma unroll
+    for (int b = 0; b < (WN + 63) / 64; ++b) {
+        const int col = b * 64 + lane;
+        reg[b] = (bias_n != nullptr && col < WN && col < n_valid) ? bias_n[col] : 0.f;
+    }
+}
+
+template <int WN>
+__device__ __forceinline__ void stage_bias(const float (&reg)[(WN + 63) / 64], float* bias_lds, int lane)
+{
+#pragma unroll
+    for (int b = 0; b < (WN + 63) / 64; ++b) {
+        const int col = b * 64 + lane;
+        if (col < WN) bias_lds[col] = reg[b];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int TN> constexpr int slab_bytes() { return 32 * (TN * 32 * 2 + 16); }
+template <int TN> constexpr int epilogue_region_bytes() { return slab_bytes<TN>() + TN * 32 * 4; }
+
+template <int TN, bool GELU>
+__device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* region, const float* bias_lds,
+                                           bf16_t* __restrict__ C, int N, int row_first, int row_end, int col_first,
+                                           int lane)
+{
+    constexpr int WN = TN * 32;
+    constexpr int PITCH = WN * 2 + 16;            // bytes; keeps 16-byte alignment, staggers banks
+    constexpr int CPR = WN / 8;                   // 16-byte chunks per slab row
+    const int m_local = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int nl = j * 32 + 8 * g + 4 * h;
+            const float4 bb = *reinterpret_cast<const float4*>(bias_lds + nl);
+            float v0 = half[j][4 * g] + bb.x, v1 = half[j][4 * g + 1] + bb.y;
+            float v2 = half[j][4 * g + 2] + bb.z, v3 = half[j][4 * g + 3] + bb.w;
+            if (GELU) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
+            uint2 packed = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+            *reinterpret_cast<uint2*>(region + m_local * PITCH + nl * 2) = packed;
+        }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int p = 0; p < (32 * CPR + 63) / 64; ++p) {
+        const int idx = lane + 64 * p;
+        const int row = idx / CPR, chunk = idx % CPR;
+        if (idx < 32 * CPR) {
+            const u32x4_v v = *reinterpret_cast<const u32x4_v*>(region + row * PITCH + chunk * 16);
+            const int r = row_first + row;
+            const int n = col_first + chunk * 8;
+            if (r < row_end && n < N) *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(r) * N + n) = v;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
 }
 
 // blockIdx -> tile index.  MAP 0: identity.  MAP 1: workgroups are handed to the 8 XCDs round

@@ -1,0 +1,286 @@
+// Wide-tile grouped bf16 GEMM for the expert FFN (Algorithm 1, "x_e <- expert(x_d)"): one workgroup
+// of four wavefronts per compute unit owns a (64 TM) x (64 TN) output tile, each wavefront a
+// (32 TM) x (32 TN) block of 32x32 MFMA tiles, so that the bytes fetched per flop fall to
+// (BM + BN) / (BM BN) -- half of what a 128 x 128 tile needs at 256 x 256 -- and the L2 -> LDS path
+// stops being the limit.
+//
+// Data path: global -> LDS directly (16 bytes per lane, 1 KiB per wavefront instruction), two
+// stages of depth 64.  The loop is scheduled by hand, one instruction per scheduling region:
+// every MFMA is followed by at most one fragment read (for the next 16-deep slice, into the other
+// fragment register set) and one direct-to-LDS load, so the matrix pipe never waits for the
+// wavefront's own memory instructions to issue.  One workgroup barrier per 64-deep step, placed
+// before the MFMAs of the last slice: at that point every wavefront has read all fragments of the
+// current stage (so the stage can be refilled) and its own loads of the next stage have landed.
+#pragma once
+#include <type_traits>
+#include "ffn_mfma.hpp"
+
+namespace dicemoe {
+
+template <int N>
+__device__ __forceinline__ void wait_lgkmcnt() {
+    __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | ((N & 0xF) << 8));
+}
+
+#define DICEMOE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int TM, int TN, int SPREAD, bool GELU, int DIAG>
+__global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
+    bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
+    const int32_t* __restrict__ seg_expert, int n_seg, int n_tiles_n, int m_tiles_max)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int WM = 32 * TM, WN = 32 * TN;
+    constexpr int CH = 8;                          // 16-byte chunks per 64-deep tile row
+    constexpr int QA = BM / 32, QB = BN / 32;      // direct-to-LDS loads per wavefront and stage (8 rows each)
+    constexpr int QW = QA + QB;
+    constexpr int STAGE = (BM + BN) * 128;         // bytes
+    constexpr int NFRAG = TM + TN;
+    constexpr int NMFMA = TM * TN;
+    constexpr int GROUP_M = 8;
+    constexpr int REGION = epilogue_region_bytes<TN>();
+    static_assert(4 * REGION <= 2 * STAGE, "epilogue slabs must fit in the stage buffers");
+    static_assert(NMFMA >= NFRAG, "one fragment read per MFMA slot");
+    static_assert(SPREAD >= 1 && SPREAD <= 4, "a refill is issued within the four slices before it is needed");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    // ---- which tile (bands of GROUP_M row tiles, XCD x takes the x-th eighth of the sequence)
+    const int t = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int band = t / (GROUP_M * n_tiles_n);
+    const int in_band = t % (GROUP_M * n_tiles_n);
+    const int left = m_tiles_max - band * GROUP_M;
+    const int rows_here = left < GROUP_M ? left : GROUP_M;
+    if (rows_here <= 0) return;
+    const int tile_m = band * GROUP_M + in_band % rows_here;
+    const int tile_n = in_band / rows_here;
+    if (tile_n >= n_tiles_n) return;
+    int seg, row0, row_end;
+    if (!find_row_tile(seg_offsets, n_seg, BM, tile_m, seg, row0, row_end)) return;
+    const int e = seg_expert[seg];
+    const int n0 = tile_n * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // bias of this wavefront's columns, fetched now and used in the epilogue
+    const int col_first = n0 + wn * WN;
+    float bias_reg[(WN + 63) / 64];
+    load_bias_columns<WN>(bias ? bias + static_cast<size_t>(e) * N + col_first : nullptr, N - col_first, lane, bias_reg);
+
+    // ---- direct-to-LDS sources.  Load q of the A part fills tile rows 8q .. 8q+7; lane l lands at
+    // LDS slot (row 8q + l/8, l%8) and therefore fetches the chunk that the swizzle assigns to that slot.
+    const char* a_base = reinterpret_cast<const char*>(A + static_cast<size_t>(row0) * K);
+    const char* w_base = reinterpret_cast<const char*>(W + (static_cast<size_t>(e) * N + n0) * K);
+    uint32_t goff[QW];
+#pragma unroll
+    for (int i = 0; i < QA; ++i) {
+        const int row = (wave * QA + i) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ chunk_swizzle<CH>(row);
+        int r = row0 + row;
+        if (r >= row_end) r = row_end - 1;                    // tail rows repeat the last row
+        goff[i] = static_cast<uint32_t>(r - row0) * static_cast<uint32_t>(K) * 2u + chunk * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < QB; ++i) {
+        const int row = (wave * QB + i) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ chunk_swizzle<CH>(row);
+        int n = n0 + row;
+        if (n >= N) n = N - 1;
+        goff[QA + i] = static_cast<uint32_t>(n - n0) * static_cast<uint32_t>(K) * 2u + chunk * 16;
+    }
+    // The k-step's 128-byte advance goes into the scalar base (kept opaque so that it stays a scalar
+    // register pair) and the per-lane part stays a 32-bit offset: the load then needs no vector
+    // address arithmetic at all.
+    auto step_base = [&](const char* base, int kt) {
+        const char* p = base + static_cast<size_t>(kt) * 128;
+        asm volatile("" : "+s"(p));
+        return p;
+    };
+    auto dma = [&](int i, int stage, const char* a_k, const char* w_k) {
+        // i < QA: A part, else W part
+        if (DIAG & 2) return;
+        uint32_t off = goff[i];
+        asm volatile("" : "+v"(off));          // keeps the zero extension next to the load (scalar base + 32-bit offset form)
+        if (i < QA)
+            __builtin_amdgcn_global_load_lds(DICEMOE_GLOBAL_PTR(a_k + off),
+                                             DICEMOE_LDS_PTR(smem + stage * STAGE + (wave * QA + i) * 1024), 16, 0, 0);
+        else
+            __builtin_amdgcn_global_load_lds(DICEMOE_GLOBAL_PTR(w_k + off),
+                                             DICEMOE_LDS_PTR(smem + stage * STAGE + BM * 128 + (wave * QB + (i - QA)) * 1024), 16, 0, 0);
+    };
+
+    // ---- fragment offsets inside a stage: 32-row blocks are 4 KiB apart, k slices differ in the chunk
+    int a_off[4], b_off[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const int chunk = kk * 2 + (lane >> 5);
+        const int ra = wm * WM + (lane & 31), rb = wn * WN + (lane & 31);
+        a_off[kk] = (ra * CH + (chunk ^ chunk_swizzle<CH>(ra))) * 16;
+        b_off[kk] = BM * 128 + (rb * CH + (chunk ^ chunk_swizzle<CH>(rb))) * 16;
+    }
+
+    f32x16_v acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    bf16x8_v fr[2][NFRAG];                           // [set][A fragments 0..TM-1, then W fragments]
+    auto read_frag = [&](int set, int f, const char* st, int kk) {
+        if (DIAG & 4) return;
+        const char* p = f < TM ? st + a_off[kk] + f * 4096 : st + b_off[kk] + (f - TM) * 4096;
+        const u32x4_v v = *reinterpret_cast<const u32x4_v*>(p);
+        fr[set][f] = *reinterpret_cast<const bf16x8_v*>(&v);
+    };
+    auto mfma = [&](int set, int m) {
+        const int i = m / TN, j = m % TN;           // operands swapped: see store_slab
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][TM + j], fr[set][i], acc[i][j], 0, 0, 0);
+    };
+
+    const int nk = K / 64;
+    // ---- prologue: both stages in flight, first fragments in registers
+    {
+        const char* a_k = step_base(a_base, 0);
+        const char* w_k = step_base(w_base, 0);
+#pragma unroll
+        for (int i = 0; i < QW; ++i) dma(i, 0, a_k, w_k);
+    }
+    if (nk > 1) {
+        const char* a_k = step_base(a_base, 1);
+        const char* w_k = step_base(w_base, 1);
+#pragma unroll
+        for (int i = 0; i < QW; ++i) dma(i, 1, a_k, w_k);
+        wait_vmcnt<QW>();
+    } else {
+        wait_vmcnt<0>();
+    }
+    block_barrier();
+#pragma unroll
+    for (int f = 0; f < NFRAG; ++f) read_frag(0, f, smem, 0);
+    if (DIAG & 4) {
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) {
+            const u32x4_v v = *reinterpret_cast<const u32x4_v*>(smem + (f < TM ? a_off[0] : b_off[0]) + (f % 4) * 4096);
+            fr[0][f] = fr[1][f] = *reinterpret_cast<const bf16x8_v*>(&v);
+        }
+    }
+
+    // One 64-deep step.  NEXT: another step follows (barrier, first fragments of the next stage).
+    // REFILL: a step after that exists too, whose stage is requested into the buffer just drained.
+    // CARRY: the previous step started a refill whose later parts are issued here.  A refill's QW
+    // loads are issued in SPREAD parts, one slice each, so that the four wavefronts do not push
+    // more loads at the texture path than it takes per slice (a full queue would stall MFMA issue).
+    constexpr int PART = (QW + SPREAD - 1) / SPREAD;
+    auto step = [&](int kt, auto next_tag, auto refill_tag, auto carry_tag) {
+        constexpr bool NEXT = decltype(next_tag)::value;
+        constexpr bool REFILL = decltype(refill_tag)::value;
+        constexpr bool CARRY = decltype(carry_tag)::value;
+        const int cur_stage = kt & 1;
+        const char* cur = smem + cur_stage * STAGE;
+        const char* nxt = smem + (cur_stage ^ 1) * STAGE;
+        const char* a_carry = step_base(a_base, kt + 1);     // the refill in flight is stage kt+1
+        const char* w_carry = step_base(w_base, kt + 1);
+        const char* a_refill = step_base(a_base, kt + 2);
+        const char* w_refill = step_base(w_base, kt + 2);
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            const int set = kk & 1;
+            DICEMOE_SCHED_FENCE();
+#pragma unroll
+            for (int m = 0; m < NMFMA; ++m) {
+                mfma(set, m);
+                DICEMOE_SCHED_FENCE();
+                if (m < NFRAG) { read_frag(set ^ 1, m, cur, kk + 1); DICEMOE_SCHED_FENCE(); }
+                if (CARRY && kk + 1 < SPREAD) {
+#pragma unroll
+                    for (int i = (kk + 1) * PART + m; i < (kk + 2) * PART && i < QW; i += NMFMA) {
+                        dma(i, cur_stage ^ 1, a_carry, w_carry);
+                        DICEMOE_SCHED_FENCE();
+                    }
+                }
+            }
+        }
+        // last slice: fragments of slice 3 are in set 1
+        DICEMOE_SCHED_FENCE();
+        if (NEXT) {
+            wait_lgkmcnt<0>();                      // every fragment of this stage has been read
+            wait_vmcnt<0>();                        // my loads of the next stage have landed
+            block_barrier();
+        }
+        DICEMOE_SCHED_FENCE();
+#pragma unroll
+        for (int m = 0; m < NMFMA; ++m) {
+            mfma(1, m);
+            DICEMOE_SCHED_FENCE();
+            if (NEXT && m < NFRAG) { read_frag(0, m, nxt, 0); DICEMOE_SCHED_FENCE(); }
+            if (REFILL) {
+#pragma unroll
+                for (int i = m; i < PART && i < QW; i += NMFMA) { dma(i, cur_stage, a_refill, w_refill); DICEMOE_SCHED_FENCE(); }
+            }
+        }
+    };
+    const std::true_type yes{};
+    const std::false_type no{};
+    if (nk == 1) {
+        step(0, no, no, no);
+    } else {
+        if (nk > 2) step(0, yes, yes, no); else step(0, yes, no, no);
+        int kt = 1;
+        for (; kt + 2 < nk; ++kt) step(kt, yes, yes, yes);
+        if (nk > 2) { step(kt, yes, no, yes); ++kt; }
+        step(kt, no, no, no);
+    }
+
+    // ---- epilogue: the stage buffers are free once every wavefront is past its last fragment read
+    wait_vmcnt<0>();
+    wait_lgkmcnt<0>();
+    block_barrier();
+    if (DIAG & 1) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s += acc[i][j][v];
+        if (s == 1234.5f) C[0] = 1;
+        return;
+    }
+    char* region = smem + wave * REGION;
+    float* bias_lds = reinterpret_cast<float*>(region + slab_bytes<TN>());
+    stage_bias<WN>(bias_reg, bias_lds, lane);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+        store_slab<TN, GELU>(acc[i], region, bias_lds, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
+}
+
+template <int TM, int TN, int SPREAD, bool GELU, int DIAG = 0>
+static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const float* bias, void* C, int N, int K,
+                                        const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
+                                        int max_rows, hipStream_t stream)
+{
+    constexpr int BM = 64 * TM, BN = 64 * TN;
+    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, GELU, DIAG>;
+    constexpr int smem = 2 * (BM + BN) * 128;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (err != hipSuccess) return err;
+        configured = true;
+    }
+    const int n_tiles_n = (N + BN - 1) / BN;
+    const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
+    const int bands = (m_tiles + 7) / 8;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n), dim3(256), smem, stream,
+                       static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, static_cast<bf16_t*>(C), N,
+                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles);
+    return hipGetLastError();
+}
+
+}  // namespace dicemoe
