@@ -104,6 +104,22 @@ class Policy:
     def c(self) -> MoePolicy:
         return MoePolicy(self.kind, self.step_t, self.stride_n, self.n_units, int(self.use_fresh_scores))
 
+    def refreshed_pairs(self, T: int, k: int) -> int:
+        """Number of (token, slot) pairs this policy refreshes among T tokens.  Every policy fixes it
+        from its parameters alone (Algorithm 4: slot 0 always, the other slots on steps with
+        t mod n == 0), so the host knows it without reading the mask back; it sizes the FFN launch."""
+        if self.kind == REFRESH_ALL:
+            return T * k
+        if self.kind == REFRESH_NONE:
+            return 0
+        if self.kind == REFRESH_ALG4:
+            return T * k if self.step_t % self.stride_n == 0 else T
+        if self.kind == REFRESH_FRACTION_TOKEN:
+            return min(max(self.n_units, 0), T) * k
+        if self.kind == REFRESH_FRACTION_PAIR:
+            return min(max(self.n_units, 0), T * k)
+        raise ValueError("unknown refresh policy %r" % (self.kind,))
+
 
 class Context:
     """Owns one ``moe_ctx``; methods carry the names of the C entry points."""
@@ -211,9 +227,12 @@ def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2
     """Enqueue one MoE layer (gate -> refresh -> dispatch -> expert FFN -> combine) on the current
     stream.  With ``policy`` None the layer is synchronous and touches no cache; otherwise the
     mask of ``policy`` is applied and ``buf`` must hold caches.  ``max_rows`` bounds the number of
-    refreshed pairs when the caller knows it (it sizes the FFN launch); default T*k."""
+    refreshed pairs (it sizes the FFN launch and picks its tile shape); by default it is the count
+    the policy implies, T*k for the synchronous layer."""
     T = x.shape[0]
     N = T * ctx.k
+    if max_rows is None and policy is not None:
+        max_rows = policy.refreshed_pairs(T, ctx.k)
     ctx.moe_gate(x, Wg, bg, buf.scores[:T], buf.expert_idx[:T], buf.probs, buf.logits)
     mask = None
     if policy is not None:

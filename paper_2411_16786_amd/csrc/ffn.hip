@@ -289,12 +289,16 @@ static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bia
 
 // Tile shape for one bf16 grouped GEMM.  The wide kernel fetches fewer bytes per flop and keeps the
 // matrix pipe fed from hand-scheduled wavefronts, and wins as soon as its tiles fill most of the chip:
-//   256 x 192 (one workgroup per compute unit) for the GEMM with the plain epilogue;
-//   128 x 192 (two workgroups per compute unit) for the GEMM whose epilogue evaluates GELU, so that one
-//   workgroup's MFMAs cover the other's epilogue arithmetic.
-// The 256 x 192 grid must cover most of the 256 compute units to pay; below that the 128 x 192 tiles
-// take over (measured down to 4096 rows at the DiT-MoE-XL widths), and tiny problems stay on the
-// 128 x 128 kernel, three workgroups per compute unit.
+//   256 x 192, two stages, one workgroup per compute unit: the GEMM with the plain epilogue, when that
+//     grid covers most of the 256 compute units;
+//   128 x 192, two stages (80 KB of LDS), two workgroups per compute unit: the GEMM whose epilogue
+//     evaluates GELU (one workgroup's MFMAs cover the other's epilogue arithmetic), and GEMMs between
+//     one and two 256-wide rounds;
+//   128 x 192, three stages, one workgroup per compute unit: grids of at most one workgroup per compute
+//     unit (few refreshed rows).  Alone on a compute unit a workgroup has nobody to hide its load
+//     latency, and the third stage gives every load two steps of flight instead of one
+//     (57 us instead of 78 us for GEMM2 at 4096 rows of the DiT-MoE-XL widths).
+// Tiny problems stay on the 128 x 128 kernel, three workgroups per compute unit.
 template <bool GELU>
 static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
@@ -308,9 +312,11 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
     };
     const bool fits_192 = (N + 191) / 192 * 192 * 8 <= N * 9;          // at most 1/8 of the columns computed in vain
     if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6)
-        return launch_gemm_bf16_wide<4, 3, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+        return launch_gemm_bf16_wide<4, 3, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+    if (fits_192 && K >= 256 && tiles(128, 192) <= kComputeUnits && tiles(128, 192) * 2 >= kComputeUnits)
+        return launch_gemm_bf16_wide<2, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
     if (fits_192 && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+        return launch_gemm_bf16_wide<2, 3, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
     return launch_gemm_bf16<128, 128, 3, true, false, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
 }
 

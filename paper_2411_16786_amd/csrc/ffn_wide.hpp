@@ -24,7 +24,7 @@ __device__ __forceinline__ void wait_lgkmcnt() {
 
 #define DICEMOE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-template <int TM, int TN, int SPREAD, bool GELU, int DIAG>
+template <int TM, int TN, int SPREAD, int STAGES, bool GELU, int DIAG>
 __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
@@ -40,7 +40,8 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     constexpr int NMFMA = TM * TN;
     constexpr int GROUP_M = 8;
     constexpr int REGION = epilogue_region_bytes<TN>();
-    static_assert(4 * REGION <= 2 * STAGE, "epilogue slabs must fit in the stage buffers");
+    static_assert(4 * REGION <= STAGES * STAGE, "epilogue slabs must fit in the stage buffers");
+    static_assert(STAGES == 2 || STAGES == 3, "ring of two or three stages");
     static_assert(NMFMA >= NFRAG, "one fragment read per MFMA slot");
     static_assert(SPREAD >= 1 && SPREAD <= 4, "a refill is issued within the four slices before it is needed");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -142,23 +143,19 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][TM + j], fr[set][i], acc[i][j], 0, 0, 0);
     };
 
-    const int nk = K / 64;
-    // ---- prologue: both stages in flight, first fragments in registers
-    {
-        const char* a_k = step_base(a_base, 0);
-        const char* w_k = step_base(w_base, 0);
+    const int nk = K / 64;                          // the launcher guarantees nk >= 4 when STAGES == 3
+    // ---- prologue: every stage in flight, first fragments in registers
 #pragma unroll
-        for (int i = 0; i < QW; ++i) dma(i, 0, a_k, w_k);
-    }
-    if (nk > 1) {
-        const char* a_k = step_base(a_base, 1);
-        const char* w_k = step_base(w_base, 1);
+    for (int s = 0; s < STAGES; ++s) {
+        if (s < nk) {
+            const char* a_k = step_base(a_base, s);
+            const char* w_k = step_base(w_base, s);
 #pragma unroll
-        for (int i = 0; i < QW; ++i) dma(i, 1, a_k, w_k);
-        wait_vmcnt<QW>();
-    } else {
-        wait_vmcnt<0>();
+            for (int i = 0; i < QW; ++i) dma(i, s, a_k, w_k);
+        }
     }
+    if (nk >= STAGES) wait_vmcnt<(STAGES - 1) * QW>();      // stage 0 has landed, the younger ones may be in flight
+    else wait_vmcnt<0>();
     block_barrier();
 #pragma unroll
     for (int f = 0; f < NFRAG; ++f) read_frag(0, f, smem, 0);
@@ -170,23 +167,29 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         }
     }
 
-    // One 64-deep step.  NEXT: another step follows (barrier, first fragments of the next stage).
-    // REFILL: a step after that exists too, whose stage is requested into the buffer just drained.
-    // CARRY: the previous step started a refill whose later parts are issued here.  A refill's QW
-    // loads are issued in SPREAD parts, one slice each, so that the four wavefronts do not push
-    // more loads at the texture path than it takes per slice (a full queue would stall MFMA issue).
+    // One 64-deep step kt, whose stage sits in ring buffer s_cur.
+    //   NEXT:   step kt+1 exists (barrier, first fragments of the next stage).
+    //   PEND:   three stages only -- the loads of stage kt+2 are in flight behind those of stage kt+1, so
+    //           the wait before the barrier lets the youngest QW loads stay outstanding (loads return
+    //           in order).
+    //   REFILL: step kt+STAGES exists; its stage is requested into the buffer this step drains.
+    //   CARRY:  the previous step started a refill whose later parts are issued here.
+    // A refill's QW loads are issued in SPREAD parts, one slice each, so that the four wavefronts do
+    // not push more loads at the texture path than it takes per slice (a full queue stalls MFMA issue).
     constexpr int PART = (QW + SPREAD - 1) / SPREAD;
-    auto step = [&](int kt, auto next_tag, auto refill_tag, auto carry_tag) {
+    auto step = [&](int kt, int s_cur, auto next_tag, auto pend_tag, auto refill_tag, auto carry_tag) {
         constexpr bool NEXT = decltype(next_tag)::value;
+        constexpr bool PEND = decltype(pend_tag)::value;
         constexpr bool REFILL = decltype(refill_tag)::value;
         constexpr bool CARRY = decltype(carry_tag)::value;
-        const int cur_stage = kt & 1;
-        const char* cur = smem + cur_stage * STAGE;
-        const char* nxt = smem + (cur_stage ^ 1) * STAGE;
-        const char* a_carry = step_base(a_base, kt + 1);     // the refill in flight is stage kt+1
-        const char* w_carry = step_base(w_base, kt + 1);
-        const char* a_refill = step_base(a_base, kt + 2);
-        const char* w_refill = step_base(w_base, kt + 2);
+        const int s_nxt = (s_cur + 1 == STAGES) ? 0 : s_cur + 1;
+        const int s_prev = (s_cur == 0) ? STAGES - 1 : s_cur - 1;
+        const char* cur = smem + s_cur * STAGE;
+        const char* nxt = smem + s_nxt * STAGE;
+        const char* a_carry = step_base(a_base, kt + STAGES - 1);   // the refill in flight fills the previous step's buffer
+        const char* w_carry = step_base(w_base, kt + STAGES - 1);
+        const char* a_refill = step_base(a_base, kt + STAGES);
+        const char* w_refill = step_base(w_base, kt + STAGES);
 #pragma unroll
         for (int kk = 0; kk < 3; ++kk) {
             const int set = kk & 1;
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
                 if (CARRY && kk + 1 < SPREAD) {
 #pragma unroll
                     for (int i = (kk + 1) * PART + m; i < (kk + 2) * PART && i < QW; i += NMFMA) {
-                        dma(i, cur_stage ^ 1, a_carry, w_carry);
+                        dma(i, s_prev, a_carry, w_carry);
                         DICEMOE_SCHED_FENCE();
                     }
                 }
@@ -209,7 +212,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         DICEMOE_SCHED_FENCE();
         if (NEXT) {
             wait_lgkmcnt<0>();                      // every fragment of this stage has been read
-            wait_vmcnt<0>();                        // my loads of the next stage have landed
+            wait_vmcnt<PEND ? QW : 0>();            // my loads of the next stage have landed
             block_barrier();
         }
         DICEMOE_SCHED_FENCE();
@@ -220,20 +223,33 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
             if (NEXT && m < NFRAG) { read_frag(0, m, nxt, 0); DICEMOE_SCHED_FENCE(); }
             if (REFILL) {
 #pragma unroll
-                for (int i = m; i < PART && i < QW; i += NMFMA) { dma(i, cur_stage, a_refill, w_refill); DICEMOE_SCHED_FENCE(); }
+                for (int i = m; i < PART && i < QW; i += NMFMA) { dma(i, s_cur, a_refill, w_refill); DICEMOE_SCHED_FENCE(); }
             }
         }
     };
     const std::true_type yes{};
     const std::false_type no{};
-    if (nk == 1) {
-        step(0, no, no, no);
+    int s_cur = 0;
+    auto advance = [&]() { s_cur = (s_cur + 1 == STAGES) ? 0 : s_cur + 1; };
+    if (STAGES == 2) {
+        if (nk == 1) {
+            step(0, 0, no, no, no, no);
+        } else {
+            if (nk > 2) step(0, 0, yes, no, yes, no); else step(0, 0, yes, no, no, no);
+            advance();
+            int kt = 1;
+            for (; kt + 2 < nk; ++kt) { step(kt, s_cur, yes, no, yes, yes); advance(); }
+            if (nk > 2) { step(kt, s_cur, yes, no, no, yes); advance(); ++kt; }
+            step(kt, s_cur, no, no, no, no);
+        }
     } else {
-        if (nk > 2) step(0, yes, yes, no); else step(0, yes, no, no);
+        step(0, 0, yes, yes, yes, no);
+        advance();
         int kt = 1;
-        for (; kt + 2 < nk; ++kt) step(kt, yes, yes, yes);
-        if (nk > 2) { step(kt, yes, no, yes); ++kt; }
-        step(kt, no, no, no);
+        for (; kt + 3 < nk; ++kt) { step(kt, s_cur, yes, yes, yes, yes); advance(); }
+        step(kt, s_cur, yes, yes, no, yes); advance(); ++kt;      // kt = nk-3
+        step(kt, s_cur, yes, no, no, no); advance(); ++kt;        // kt = nk-2
+        step(kt, s_cur, no, no, no, no);                          // kt = nk-1
     }
 
     // ---- epilogue: the stage buffers are free once every wavefront is past its last fragment read
@@ -259,14 +275,15 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         store_slab<TN, GELU>(acc[i], region, bias_lds, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
 }
 
-template <int TM, int TN, int SPREAD, bool GELU, int DIAG = 0>
+template <int TM, int TN, int SPREAD, int STAGES, bool GELU, int DIAG = 0>
 static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, GELU, DIAG>;
-    constexpr int smem = 2 * (BM + BN) * 128;
+    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, STAGES, GELU, DIAG>;
+    constexpr int smem = STAGES * (BM + BN) * 128;
+    if (STAGES == 3 && K < 4 * 64) return hipErrorInvalidValue;      // the three-stage loop is written for at least four steps
     static bool configured = false;
     if (!configured) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

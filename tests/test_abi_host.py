@@ -105,3 +105,23 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(8, 64)
     with pytest.raises(ValueError):
         ctx.moe_gate(x, x, None, x, x)
+
+
+def test_policy_row_count_matches_the_oracle_mask():
+    """The binding sizes the FFN launch from the policy alone; the count it derives must equal the
+    number of pairs the oracle's mask (Algorithm 4 and the fraction forms) actually refreshes."""
+    import numpy as np
+    from oracle import moe_oracle as O
+
+    rng = np.random.default_rng(7)
+    for T, k in ((1, 1), (5, 2), (64, 2), (33, 3)):
+        s = rng.random((T, k))
+        s = -np.sort(-s, axis=1)            # slot 0 carries the largest score, as the router emits them
+        cases = [B.Policy(B.REFRESH_ALL), B.Policy(B.REFRESH_NONE)]
+        cases += [B.Policy(B.REFRESH_ALG4, step_t=t, stride_n=n) for n in (1, 2, 3) for t in range(4)]
+        cases += [B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=u) for u in (0, 1, T // 2, T)]
+        cases += [B.Policy(B.REFRESH_FRACTION_PAIR, n_units=u) for u in (0, 1, T, T * k // 2 + 1, T * k)]
+        for pol in cases:
+            mask, R = O.refresh_mask(s, pol.kind, pol.step_t, pol.stride_n, pol.n_units)
+            assert R == int(mask.sum())
+            assert pol.refreshed_pairs(T, k) == R, (T, k, pol)

@@ -208,6 +208,52 @@ def test_expert_ffn_against_oracle(case):
     assert (h_gpu[rows:] == 9.0).all()          # rows outside every segment are left untouched
 
 
+# Shapes that take each launch configuration of the wide-tile bf16 kernel (tile shape, number of
+# stages, workgroups per compute unit are chosen from rows and widths), checked on sampled rows:
+# the first and last rows of every segment (tile and segment boundaries) plus random ones.
+WIDE_FFN_CASES = [
+    # (name, rows per segment, d, F)
+    ("xl-8192-rows", [1391, 612, 1204, 893, 1347, 701, 1120, 924], 1152, 4608),   # 128x192 x2 / 256x192
+    ("xl-4096-rows", [695, 306, 602, 446, 673, 350, 560, 464], 1152, 4608),       # 128x192 x2 / three stages
+    ("xl-700-rows", [3, 250, 0, 129, 64, 1, 192, 61], 1152, 4608),                # three stages / 128x128
+    ("column-tails", [700, 0, 1033, 515, 390, 462], 1088, 1600),                  # widths not multiples of 192
+]
+
+
+@pytest.mark.parametrize("case", WIDE_FFN_CASES, ids=[c[0] for c in WIDE_FFN_CASES])
+def test_expert_ffn_wide_tiles_on_sampled_rows(case):
+    name, seg_rows, d, F = case
+    say(f"wide ffn case {name}")
+    dtype = "bf16"
+    E = len(seg_rows)
+    rows = int(sum(seg_rows))
+    # weights of the order of 1/sqrt(fan-in), as in the workloads: outputs of order one, for which the
+    # absolute bf16 tolerance is written
+    _, _, _, W1, b1, W2, b2 = G.small_inputs(51, 4, d, E, F, dtype, bias=True, w_std=0.02)
+    r = np.random.Generator(np.random.PCG64(52))
+    xp = WL.to_storage(r.standard_normal((rows, d), dtype=np.float32), dtype)
+    seg_expert = np.roll(np.arange(E, dtype=np.int32), 3)
+    seg_offsets = np.concatenate([[0], np.cumsum(seg_rows)]).astype(np.int32)
+    ctx = B.Context(rows + 8, d, F, E, 1, dtype)
+    h = torch.full((rows + 8, d), 9.0, dtype=ctx.torch_dtype, device=G.DEV)
+    xp_dev = torch.zeros((rows + 8, d), dtype=ctx.torch_dtype, device=G.DEV)
+    xp_dev[:rows] = G.to_dev(xp, dtype)
+    ws = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=G.DEV)
+    ctx.moe_expert_ffn(xp_dev, G.i32_dev(seg_offsets), G.i32_dev(seg_expert), rows, G.to_dev(W1, dtype),
+                       G.f32_dev(b1), G.to_dev(W2, dtype), G.f32_dev(b2), h, ws)
+    torch.cuda.synchronize()
+    h_gpu = G.to_np(h)
+    edge = []
+    for g in range(E):
+        lo, hi = int(seg_offsets[g]), int(seg_offsets[g + 1])
+        edge += [q for q in (lo, lo + 1, hi - 2, hi - 1) if lo <= q < hi]
+    sel = np.unique(np.concatenate([np.array(edge, dtype=np.int64), r.integers(0, rows, 160)])).astype(np.int32)
+    h_ref = O.expert_ffn(xp, seg_offsets, seg_expert, W1, b1, W2, b2, rows_sel=sel)
+    G.assert_close_storage(h_gpu[sel], h_ref, dtype, name)
+    assert (h_gpu[rows:] == 9.0).all()          # rows outside every segment are left untouched
+    assert np.isfinite(h_gpu[:rows]).all() and (h_gpu[:rows] != 9.0).any(axis=1).all()   # every row written
+
+
 # ----------------------------------------------------------------------------- combine
 @pytest.mark.parametrize("T,k,d,dtype", [(64, 2, 64, "f32"), (333, 3, 128, "bf16"), (4096, 2, 1152, "bf16")])
 def test_combine_against_oracle_on_the_same_rows(T, k, d, dtype):
