@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--refresh-sweep", action="store_true",
                     help="also time the 512px conditional-communication workload (T=8192) at refresh fractions "
                          "25/50/75/100 %% and report it under 'conditional_refresh'")
+    ap.add_argument("--packed-dispatch", action="store_true",
+                    help="materialise x_packed in moe_dispatch instead of gathering rows in the FFN's operand load")
     ap.add_argument("--eager", action="store_true", help="launch from Python every step instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -75,7 +77,8 @@ def main():
 
     def one_step():
         for L in layers:
-            B.moe_layer_forward(ctx, L["buf"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None)
+            B.moe_layer_forward(ctx, L["buf"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None,
+                                fuse_gather=not args.packed_dispatch)
 
     # ---- optional HIP graph of one step (the launch sequence is static)
     graph = None
@@ -120,11 +123,12 @@ def main():
             ev[0].record()
             ctx.moe_gate(L["x"], L["Wg"], L["bg"], buf.scores, buf.expert_idx)
             ev[1].record()
-            ctx.moe_dispatch(L["x"], buf.expert_idx, None, buf.x_packed, buf.counts, buf.offsets, buf.perm,
+            # as in moe_layer_forward: dispatch writes the index outputs, the FFN gathers the rows itself
+            ctx.moe_dispatch(L["x"], buf.expert_idx, None, None, buf.counts, buf.offsets, buf.perm,
                              buf.inv, buf.workspace)
             ev[2].record()
-            ctx.moe_expert_ffn(buf.x_packed, buf.offsets, buf.seg_expert, N, L["W1"], None, L["W2"], None,
-                               buf.h_packed, buf.workspace)
+            ctx.moe_expert_ffn_rows(L["x"], buf.perm, buf.offsets, buf.seg_expert, N, L["W1"], None, L["W2"], None,
+                                    buf.h_packed, buf.workspace)
             ev[3].record()
             ctx.moe_combine(buf.h_packed, buf.inv, buf.scores, None, None, None, False, buf.y)
             ev[4].record()
@@ -137,7 +141,7 @@ def main():
     b = 2
     alg_bytes = {
         "gate": T * d * b + E * d * b + T * k * 8,
-        "dispatch": T * d * b + N * d * b + 16 * N,
+        "dispatch": 16 * N,          # index outputs only; the row gather rides in the FFN's operand load
         "combine": N * d * b + T * d * b + T * k * 9,
     }
     ffn_flops = 4.0 * N * d * F

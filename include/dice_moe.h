@@ -129,7 +129,9 @@ int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* ex
  *   out: x_packed[R][d] rows of the refreshed pairs ordered by (expert asc, pair id asc), copied
  *        bit for bit (rows >= R are left untouched); counts[E]; offsets[E+1] exclusive prefix
  *        sums (offsets[E] = R); perm[T*k]: pair id of packed row r, -1 for r >= R;
- *        inv[T*k]: packed row of pair p, -1 if p is not refreshed. */
+ *        inv[T*k]: packed row of pair p, -1 if p is not refreshed.
+ * x_packed may be NULL: then only the index outputs are written (x is not read and may be NULL too)
+ * and the rows are gathered by the consumer, see moe_expert_ffn_rows. */
 int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const uint8_t* mask,
                  int32_t T, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
                  int32_t* inv, void* workspace, void* stream);
@@ -150,6 +152,18 @@ int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* seg_offset
                    const int32_t* seg_expert, int32_t n_segments, int32_t max_rows,
                    const void* W1, const float* b1, const void* W2, const float* b2,
                    void* h_packed, void* workspace, void* stream);
+
+/* The same expert FFN with the dispatch gather folded into its first operand load (single-device
+ * path of Algorithm 1: dispatch and expert on one device need no send buffer): packed row r is read
+ * from x[row_pairs[r] / k], where row_pairs is the perm output of moe_dispatch (pair id of packed
+ * row r), so x_packed is never materialised.  Results are bit-identical to moe_dispatch with a packed
+ * buffer followed by moe_expert_ffn.
+ *   in : x[T][d] (dtype); row_pairs[>= seg_offsets[n_segments]] (device), every entry in 0..T*k-1;
+ *        the other arguments as for moe_expert_ffn */
+int moe_expert_ffn_rows(moe_ctx* ctx, const void* x, const int32_t* row_pairs,
+                        const int32_t* seg_offsets, const int32_t* seg_expert, int32_t n_segments,
+                        int32_t max_rows, const void* W1, const float* b1, const void* W2,
+                        const float* b2, void* h_packed, void* workspace, void* stream);
 
 /* Combine + scale + cache blend (Algorithm 1 combine/scale; Algorithm 4 "reuse stale h"):
  *   y_i = sum_{j=0..k-1} s*_ij h*_ij   accumulated in float in slot order,

@@ -25,8 +25,8 @@ MOE_ERR_NULL, MOE_ERR_SHAPE, MOE_ERR_DTYPE, MOE_ERR_POLICY = -1, -2, -3, -4
 MOE_ERR_WORKSPACE, MOE_ERR_CACHE_COLD, MOE_ERR_HIP = -5, -6, -7
 
 EXPORTS = ["moe_create", "moe_destroy", "moe_workspace_bytes", "moe_last_error", "moe_status_string",
-           "moe_gate", "moe_conditional_refresh", "moe_dispatch", "moe_expert_ffn", "moe_combine",
-           "moe_ep_segments"]
+           "moe_gate", "moe_conditional_refresh", "moe_dispatch", "moe_expert_ffn", "moe_expert_ffn_rows",
+           "moe_combine", "moe_ep_segments"]
 
 
 class MoeShape(ctypes.Structure):
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
         L.moe_conditional_refresh.argtypes = [vp, vp, vp, i32, ctypes.POINTER(MoePolicy), vp, vp, vp, vp]
         L.moe_dispatch.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.moe_expert_ffn_rows.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_combine.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
         L.moe_ep_segments.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         for name in EXPORTS:
@@ -179,6 +180,15 @@ class Context:
                                          _ptr(W2, self.torch_dtype), _ptr(b2, torch.float32),
                                          _ptr(h_packed, self.torch_dtype), _ptr(workspace), _stream()))
 
+    def moe_expert_ffn_rows(self, x, row_pairs, seg_offsets, seg_expert, max_rows, W1, b1, W2, b2, h_packed,
+                            workspace):
+        n_seg = seg_expert.shape[0]
+        self._check(lib().moe_expert_ffn_rows(self._h, _ptr(x, self.torch_dtype), _ptr(row_pairs, torch.int32),
+                                              _ptr(seg_offsets, torch.int32), _ptr(seg_expert, torch.int32), n_seg,
+                                              max_rows, _ptr(W1, self.torch_dtype), _ptr(b1, torch.float32),
+                                              _ptr(W2, self.torch_dtype), _ptr(b2, torch.float32),
+                                              _ptr(h_packed, self.torch_dtype), _ptr(workspace), _stream()))
+
     def moe_combine(self, h_packed, inv, scores, mask, H_cache, S_cache, use_fresh_scores, y):
         T = scores.shape[0]
         self._check(lib().moe_combine(self._h, _ptr(h_packed, self.torch_dtype), _ptr(inv, torch.int32),
@@ -223,12 +233,14 @@ class LayerBuffers:
 
 
 def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2,
-                      policy: Optional[Policy] = None, max_rows: Optional[int] = None):
+                      policy: Optional[Policy] = None, max_rows: Optional[int] = None, fuse_gather: bool = True):
     """Enqueue one MoE layer (gate -> refresh -> dispatch -> expert FFN -> combine) on the current
     stream.  With ``policy`` None the layer is synchronous and touches no cache; otherwise the
     mask of ``policy`` is applied and ``buf`` must hold caches.  ``max_rows`` bounds the number of
     refreshed pairs (it sizes the FFN launch and picks its tile shape); by default it is the count
-    the policy implies, T*k for the synchronous layer."""
+    the policy implies, T*k for the synchronous layer.  With ``fuse_gather`` (default) dispatch
+    writes its index outputs only and the FFN reads the token rows through ``perm``; otherwise
+    ``buf.x_packed`` is materialised first (the send buffer of the expert-parallel layout)."""
     T = x.shape[0]
     N = T * ctx.k
     if max_rows is None and policy is not None:
@@ -239,10 +251,17 @@ def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2
         ctx.moe_conditional_refresh(buf.scores[:T], buf.expert_idx[:T], policy, buf.mask[:T], buf.n_refresh,
                                     buf.workspace)
         mask = buf.mask[:T]
-    ctx.moe_dispatch(x, buf.expert_idx[:T], mask, buf.x_packed, buf.counts, buf.offsets, buf.perm, buf.inv,
-                     buf.workspace)
-    ctx.moe_expert_ffn(buf.x_packed, buf.offsets, buf.seg_expert, N if max_rows is None else max_rows,
-                       W1, b1, W2, b2, buf.h_packed, buf.workspace)
+    rows = N if max_rows is None else max_rows
+    if fuse_gather:
+        ctx.moe_dispatch(x, buf.expert_idx[:T], mask, None, buf.counts, buf.offsets, buf.perm, buf.inv,
+                         buf.workspace)
+        ctx.moe_expert_ffn_rows(x, buf.perm, buf.offsets, buf.seg_expert, rows, W1, b1, W2, b2, buf.h_packed,
+                                buf.workspace)
+    else:
+        ctx.moe_dispatch(x, buf.expert_idx[:T], mask, buf.x_packed, buf.counts, buf.offsets, buf.perm, buf.inv,
+                         buf.workspace)
+        ctx.moe_expert_ffn(buf.x_packed, buf.offsets, buf.seg_expert, rows, W1, b1, W2, b2, buf.h_packed,
+                           buf.workspace)
     use_fresh = bool(policy.use_fresh_scores) if policy is not None else False
     ctx.moe_combine(buf.h_packed, buf.inv, buf.scores[:T], mask,
                     buf.H_cache if policy is not None else None,

@@ -170,7 +170,7 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const u
     (void)workspace;
     if (!ctx) return MOE_ERR_NULL;
     if (int rc = check_T(ctx, T)) return rc;
-    if (!x || !expert_idx || !x_packed || !counts || !offsets || !perm || !inv)
+    if (!expert_idx || !counts || !offsets || !perm || !inv || (x_packed && !x))
         return fail(ctx, MOE_ERR_NULL, "moe_dispatch: null pointer");
     const moe_shape& s = ctx->shape;
     return hip_result(ctx,
@@ -179,23 +179,53 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const u
                       "moe_dispatch");
 }
 
-int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* seg_offsets, const int32_t* seg_expert,
-                   int32_t n_segments, int32_t max_rows, const void* W1, const float* b1, const void* W2,
-                   const float* b2, void* h_packed, void* workspace, void* stream)
+}  // extern "C"
+
+static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, const int32_t* row_pairs,
+                             const int32_t* seg_offsets, const int32_t* seg_expert, int32_t n_segments,
+                             int32_t max_rows, const void* W1, const float* b1, const void* W2, const float* b2,
+                             void* h_packed, void* workspace, void* stream)
 {
-    if (!ctx) return MOE_ERR_NULL;
     const moe_shape& s = ctx->shape;
     if (n_segments < 1 || n_segments > 1024)
         return fail(ctx, MOE_ERR_SHAPE, "n_segments=%ld outside 1..1024", n_segments);
     if (max_rows < 0 || static_cast<long long>(max_rows) > static_cast<long long>(s.T_max) * s.k)
         return fail(ctx, MOE_ERR_SHAPE, "max_rows=%ld outside 0..T_max*k=%ld", max_rows, static_cast<long>(s.T_max) * s.k);
-    if (!x_packed || !seg_offsets || !seg_expert || !W1 || !W2 || !h_packed)
-        return fail(ctx, MOE_ERR_NULL, "moe_expert_ffn: null pointer");
-    if (!workspace) return fail(ctx, MOE_ERR_WORKSPACE, "moe_expert_ffn: workspace is null");
+    if (!x_rows || !seg_offsets || !seg_expert || !W1 || !W2 || !h_packed) {
+        std::snprintf(ctx->err, sizeof(ctx->err), "%s: null pointer", who);
+        return MOE_ERR_NULL;
+    }
+    if (!workspace) {
+        std::snprintf(ctx->err, sizeof(ctx->err), "%s: workspace is null", who);
+        return MOE_ERR_WORKSPACE;
+    }
     return hip_result(ctx,
-                      launch_expert_ffn(is_bf16(ctx), x_packed, seg_offsets, seg_expert, n_segments, max_rows, s.d,
-                                        s.F, W1, b1, W2, b2, h_packed, workspace, static_cast<hipStream_t>(stream)),
-                      "moe_expert_ffn");
+                      launch_expert_ffn(is_bf16(ctx), x_rows, row_pairs, s.k, seg_offsets, seg_expert, n_segments,
+                                        max_rows, s.d, s.F, W1, b1, W2, b2, h_packed, workspace,
+                                        static_cast<hipStream_t>(stream)),
+                      who);
+}
+
+extern "C" {
+
+int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* seg_offsets, const int32_t* seg_expert,
+                   int32_t n_segments, int32_t max_rows, const void* W1, const float* b1, const void* W2,
+                   const float* b2, void* h_packed, void* workspace, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    return expert_ffn_common(ctx, "moe_expert_ffn", x_packed, nullptr, seg_offsets, seg_expert, n_segments, max_rows, W1,
+                             b1, W2, b2, h_packed, workspace, stream);
+}
+
+int moe_expert_ffn_rows(moe_ctx* ctx, const void* x, const int32_t* row_pairs, const int32_t* seg_offsets,
+                        const int32_t* seg_expert, int32_t n_segments, int32_t max_rows, const void* W1,
+                        const float* b1, const void* W2, const float* b2, void* h_packed, void* workspace,
+                        void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (!row_pairs) return fail(ctx, MOE_ERR_NULL, "moe_expert_ffn_rows: row_pairs is null");
+    return expert_ffn_common(ctx, "moe_expert_ffn_rows", x, row_pairs, seg_offsets, seg_expert, n_segments, max_rows, W1,
+                             b1, W2, b2, h_packed, workspace, stream);
 }
 
 int moe_combine(moe_ctx* ctx, const void* h_packed, const int32_t* inv, const float* scores, const uint8_t* mask,

@@ -183,7 +183,7 @@ hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const u
     hipLaunchKernelGGL(dispatch_index_kernel, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
                        offsets, perm, inv);
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess || T_tok == 0) return err;
+    if (err != hipSuccess || T_tok == 0 || x_packed == nullptr) return err;   // no packed buffer: index only
     const int blocks = (T_tok + 3) / 4;
     if (bf16)
         hipLaunchKernelGGL(dispatch_gather_kernel<bf16_t>, dim3(blocks), dim3(256), 0, stream,

@@ -32,7 +32,8 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
                                                                  bf16_t* __restrict__ C, int N, int K,
                                                                  const int32_t* __restrict__ seg_offsets,
                                                                  const int32_t* __restrict__ seg_expert, int n_seg,
-                                                                 int n_tiles_n, int m_tiles_max)
+                                                                 int n_tiles_n, int m_tiles_max,
+                                                                 const int32_t* __restrict__ row_index, int row_div)
 {
     constexpr int BK = 64;
     constexpr int CH = BK / 8;          // 16-byte chunks per tile row
@@ -85,6 +86,7 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
     for (int p = 0; p < A_PASSES; ++p) {
         int r = row0 + ld_row + 32 * p;
         if (r >= row_end) r = row_end - 1;                    // clamp: tail rows repeat the last row
+        if (row_index) r = row_index[r] / row_div;            // gather folded into the operand load
         a_src[p] = reinterpret_cast<const u32x4_v*>(A + static_cast<size_t>(r) * K) + ld_chunk;
     }
 #pragma unroll
@@ -198,7 +200,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
                                                            const float* __restrict__ bias, float* __restrict__ C,
                                                            int N, int K, const int32_t* __restrict__ seg_offsets,
                                                            const int32_t* __restrict__ seg_expert, int n_seg,
-                                                           int n_tiles_n)
+                                                           int n_tiles_n, const int32_t* __restrict__ row_index,
+                                                           int row_div)
 {
     constexpr int BM = 64, BN = 64, BK = 16;
     __shared__ float As[BK][BM + 4];
@@ -215,6 +218,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
     const int ld_r = tid >> 2, ld_c = (tid & 3) * 4;  // 64 rows x 4 float4 per tile
 
     int ar = row0 + ld_r; if (ar >= row_end) ar = row_end - 1;
+    if (row_index) ar = row_index[ar] / row_div;
     int bn = n0 + ld_r;   if (bn >= N) bn = N - 1;
     const float* a_src = A + static_cast<size_t>(ar) * K + ld_c;
     const float* b_src = We + static_cast<size_t>(bn) * K + ld_c;
@@ -263,27 +267,28 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
 template <int BM, int BN, int OCC, bool XCD, bool PF, bool GELU>
 static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                    const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
-                                   hipStream_t stream)
+                                   hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1)
 {
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
     const int bands = (m_tiles + 7) / 8;
     hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, OCC, XCD, PF, GELU>), dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n),
                        dim3(256), 0, stream, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias,
-                       static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles);
+                       static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index,
+                       row_div);
     return hipGetLastError();
 }
 
 template <bool GELU>
 static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                   const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
-                                  hipStream_t stream)
+                                  hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1)
 {
     const int n_tiles_n = (N + 63) / 64;
     const int m_tiles = (max_rows + 63) / 64 + n_seg;
     hipLaunchKernelGGL((ffn_gemm_f32_kernel<GELU>), dim3(static_cast<unsigned>(m_tiles) * n_tiles_n), dim3(256), 0,
                        stream, static_cast<const float*>(A), static_cast<const float*>(W), bias,
-                       static_cast<float*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n);
+                       static_cast<float*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, row_index, row_div);
     return hipGetLastError();
 }
 
@@ -302,7 +307,8 @@ static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bia
 template <bool GELU>
 static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
-                                        int max_rows, hipStream_t stream)
+                                        int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
+                                        int row_div = 1)
 {
     constexpr int kComputeUnits = 256;
     // expected tiles: every segment ends in a partial row tile, half a tile on average
@@ -312,27 +318,30 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
     };
     const bool fits_192 = (N + 191) / 192 * 192 * 8 <= N * 9;          // at most 1/8 of the columns computed in vain
     if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6)
-        return launch_gemm_bf16_wide<4, 3, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+        return launch_gemm_bf16_wide<4, 3, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
     if (fits_192 && K >= 256 && tiles(128, 192) <= kComputeUnits && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+        return launch_gemm_bf16_wide<2, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
     if (fits_192 && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
-    return launch_gemm_bf16<128, 128, 3, true, false, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream);
+        return launch_gemm_bf16_wide<2, 3, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
+    return launch_gemm_bf16<128, 128, 3, true, false, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
+                                                           row_div);
 }
 
-hipError_t launch_expert_ffn(bool bf16, const void* x_packed, const int32_t* seg_offsets,
-                             const int32_t* seg_expert, int n_seg, int max_rows, int d, int F, const void* W1,
-                             const float* b1, const void* W2, const float* b2, void* h_packed, void* hidden,
-                             hipStream_t stream)
+hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_index, int row_div,
+                             const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
+                             int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_packed,
+                             void* hidden, hipStream_t stream)
 {
     if (max_rows == 0) return hipSuccess;
     hipError_t err;
     if (bf16) {
-        err = launch_gemm_bf16_auto<true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream);
+        err = launch_gemm_bf16_auto<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream,
+                                          row_index, row_div);
         if (err != hipSuccess) return err;
         return launch_gemm_bf16_auto<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream);
     }
-    err = launch_gemm_f32<true>(x_packed, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream);
+    err = launch_gemm_f32<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
+                                row_div);
     if (err != hipSuccess) return err;
     return launch_gemm_f32<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream);
 }

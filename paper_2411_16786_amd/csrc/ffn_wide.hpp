@@ -28,7 +28,8 @@ template <int TM, int TN, int SPREAD, int STAGES, bool GELU, int DIAG>
 __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
-    const int32_t* __restrict__ seg_expert, int n_seg, int n_tiles_n, int m_tiles_max)
+    const int32_t* __restrict__ seg_expert, int n_seg, int n_tiles_n, int m_tiles_max,
+    const int32_t* __restrict__ row_index, int row_div)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int WM = 32 * TM, WN = 32 * TN;
@@ -73,7 +74,9 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
 
     // ---- direct-to-LDS sources.  Load q of the A part fills tile rows 8q .. 8q+7; lane l lands at
     // LDS slot (row 8q + l/8, l%8) and therefore fetches the chunk that the swizzle assigns to that slot.
-    const char* a_base = reinterpret_cast<const char*>(A + static_cast<size_t>(row0) * K);
+    // With a row index, packed row r is read from A row row_index[r] / row_div (the pair id of
+    // the packed row divided by k is its token): the dispatch gather folded into the operand load.
+    const char* a_base = reinterpret_cast<const char*>(A);
     const char* w_base = reinterpret_cast<const char*>(W + (static_cast<size_t>(e) * N + n0) * K);
     uint32_t goff[QW];
 #pragma unroll
@@ -82,7 +85,8 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         const int chunk = (lane & 7) ^ chunk_swizzle<CH>(row);
         int r = row0 + row;
         if (r >= row_end) r = row_end - 1;                    // tail rows repeat the last row
-        goff[i] = static_cast<uint32_t>(r - row0) * static_cast<uint32_t>(K) * 2u + chunk * 16;
+        const uint32_t src = row_index ? static_cast<uint32_t>(row_index[r] / row_div) : static_cast<uint32_t>(r);
+        goff[i] = src * static_cast<uint32_t>(K) * 2u + chunk * 16;     // the launcher checks that A spans < 4 GiB
     }
 #pragma unroll
     for (int i = 0; i < QB; ++i) {
@@ -144,17 +148,23 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     };
 
     const int nk = K / 64;                          // the launcher guarantees nk >= 4 when STAGES == 3
-    // ---- prologue: every stage in flight, first fragments in registers
+    // ---- prologue: every stage in flight, first fragments in registers.  The W parts go first: they
+    // do not depend on the row index, whose load is still in flight when a gathering kernel gets here.
 #pragma unroll
-    for (int s = 0; s < STAGES; ++s) {
-        if (s < nk) {
-            const char* a_k = step_base(a_base, s);
-            const char* w_k = step_base(w_base, s);
+    for (int part = 0; part < 2; ++part) {
 #pragma unroll
-            for (int i = 0; i < QW; ++i) dma(i, s, a_k, w_k);
+        for (int s = 0; s < STAGES; ++s) {
+            if (s < nk) {
+                const char* a_k = step_base(a_base, s);
+                const char* w_k = step_base(w_base, s);
+#pragma unroll
+                for (int i = (part == 0 ? QA : 0); i < (part == 0 ? QW : QA); ++i) dma(i, s, a_k, w_k);
+            }
         }
     }
-    if (nk >= STAGES) wait_vmcnt<(STAGES - 1) * QW>();      // stage 0 has landed, the younger ones may be in flight
+    // loads return in order: stage 0 is complete once its A part is, i.e. when at most the A parts of
+    // the younger stages are outstanding
+    if (nk >= STAGES) wait_vmcnt<(STAGES - 1) * QA>();
     else wait_vmcnt<0>();
     block_barrier();
 #pragma unroll
@@ -177,7 +187,8 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     // A refill's QW loads are issued in SPREAD parts, one slice each, so that the four wavefronts do
     // not push more loads at the texture path than it takes per slice (a full queue stalls MFMA issue).
     constexpr int PART = (QW + SPREAD - 1) / SPREAD;
-    auto step = [&](int kt, int s_cur, auto next_tag, auto pend_tag, auto refill_tag, auto carry_tag) {
+    auto step = [&](int kt, int s_cur, auto next_tag, auto pend_tag, auto refill_tag, auto carry_tag, auto first_tag) {
+        constexpr bool FIRST = decltype(first_tag)::value;     // step 0: the prologue issued the A parts last
         constexpr bool NEXT = decltype(next_tag)::value;
         constexpr bool PEND = decltype(pend_tag)::value;
         constexpr bool REFILL = decltype(refill_tag)::value;
@@ -212,7 +223,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         DICEMOE_SCHED_FENCE();
         if (NEXT) {
             wait_lgkmcnt<0>();                      // every fragment of this stage has been read
-            wait_vmcnt<PEND ? QW : 0>();            // my loads of the next stage have landed
+            wait_vmcnt<PEND ? (FIRST ? QA : QW) : 0>();   // my loads of the next stage have landed
             block_barrier();
         }
         DICEMOE_SCHED_FENCE();
@@ -233,23 +244,23 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     auto advance = [&]() { s_cur = (s_cur + 1 == STAGES) ? 0 : s_cur + 1; };
     if (STAGES == 2) {
         if (nk == 1) {
-            step(0, 0, no, no, no, no);
+            step(0, 0, no, no, no, no, yes);
         } else {
-            if (nk > 2) step(0, 0, yes, no, yes, no); else step(0, 0, yes, no, no, no);
+            if (nk > 2) step(0, 0, yes, no, yes, no, yes); else step(0, 0, yes, no, no, no, yes);
             advance();
             int kt = 1;
-            for (; kt + 2 < nk; ++kt) { step(kt, s_cur, yes, no, yes, yes); advance(); }
-            if (nk > 2) { step(kt, s_cur, yes, no, no, yes); advance(); ++kt; }
-            step(kt, s_cur, no, no, no, no);
+            for (; kt + 2 < nk; ++kt) { step(kt, s_cur, yes, no, yes, yes, no); advance(); }
+            if (nk > 2) { step(kt, s_cur, yes, no, no, yes, no); advance(); ++kt; }
+            step(kt, s_cur, no, no, no, no, no);
         }
     } else {
-        step(0, 0, yes, yes, yes, no);
+        step(0, 0, yes, yes, yes, no, yes);
         advance();
         int kt = 1;
-        for (; kt + 3 < nk; ++kt) { step(kt, s_cur, yes, yes, yes, yes); advance(); }
-        step(kt, s_cur, yes, yes, no, yes); advance(); ++kt;      // kt = nk-3
-        step(kt, s_cur, yes, no, no, no); advance(); ++kt;        // kt = nk-2
-        step(kt, s_cur, no, no, no, no);                          // kt = nk-1
+        for (; kt + 3 < nk; ++kt) { step(kt, s_cur, yes, yes, yes, yes, no); advance(); }
+        step(kt, s_cur, yes, yes, no, yes, no); advance(); ++kt;      // kt = nk-3
+        step(kt, s_cur, yes, no, no, no, no); advance(); ++kt;        // kt = nk-2
+        step(kt, s_cur, no, no, no, no, no);                          // kt = nk-1
     }
 
     // ---- epilogue: the stage buffers are free once every wavefront is past its last fragment read
@@ -278,7 +289,8 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
 template <int TM, int TN, int SPREAD, int STAGES, bool GELU, int DIAG = 0>
 static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
-                                        int max_rows, hipStream_t stream)
+                                        int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
+                                        int row_div = 1)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, STAGES, GELU, DIAG>;
@@ -296,7 +308,7 @@ static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const floa
     const int bands = (m_tiles + 7) / 8;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n), dim3(256), smem, stream,
                        static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, static_cast<bf16_t*>(C), N,
-                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles);
+                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index, row_div);
     return hipGetLastError();
 }
 

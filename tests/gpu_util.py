@@ -125,8 +125,9 @@ class GpuLayer:
         self.b2 = f32_dev(b2)
         self.buf = B.LayerBuffers(self.ctx, DEV, with_cache=with_cache, with_debug=True)
 
-    def forward(self, policy=None, x=None):
+    def forward(self, policy=None, x=None, fuse_gather=False):
+        # x_packed is materialised by default here: the stage checks read it back
         y = B.moe_layer_forward(self.ctx, self.buf, self.x if x is None else x, self.Wg, self.bg,
-                                self.W1, self.b1, self.W2, self.b2, policy)
+                                self.W1, self.b1, self.W2, self.b2, policy, fuse_gather=fuse_gather)
         torch.cuda.synchronize()
         return y

@@ -94,6 +94,10 @@ def test_host_detectable_errors_return_before_any_launch():
     assert L.moe_expert_ffn(h, one, one, one, 0, 8, one, None, one, None, one, one, None) == B.MOE_ERR_SHAPE
     assert L.moe_expert_ffn(h, one, one, one, 4, 129, one, None, one, None, one, one, None) == B.MOE_ERR_SHAPE
     assert L.moe_expert_ffn(h, one, one, one, 4, 8, one, None, one, None, one, None, None) == B.MOE_ERR_WORKSPACE
+    assert L.moe_expert_ffn_rows(h, one, None, one, one, 4, 8, one, None, one, None, one, one, None) == B.MOE_ERR_NULL
+    assert b"row_pairs" in L.moe_last_error(h)
+    assert L.moe_expert_ffn_rows(h, one, one, one, one, 4, 129, one, None, one, None, one, one, None) == B.MOE_ERR_SHAPE
+    assert L.moe_dispatch(h, None, one, None, 8, one, one, one, one, one, None, None) == B.MOE_ERR_NULL  # rows wanted, no x
     assert L.moe_ep_segments(h, one, 4, 8, one, one, None) == B.MOE_ERR_SHAPE     # E_loc > E
     # T = 0 launches nothing
     assert L.moe_gate(h, one, one, None, 0, one, one, None, None, None) == B.MOE_OK

@@ -331,6 +331,45 @@ def test_layer_config2_small_bf16():
     assert load.max() < 1.5          # near-uniform load
 
 
+@pytest.mark.parametrize("cfg,T", [(1, None), (2, None), (3, None), (3, 1500)])
+def test_layer_forward_with_the_gather_folded_into_the_ffn(cfg, T):
+    """moe_layer_forward's default path (dispatch writes indices only, the first GEMM reads token rows
+    through perm) against the path that materialises x_packed: bit-identical h rows and y, for the
+    synchronous layer and for an Algorithm 4 off-step; and y against the oracle where it runs in full."""
+    li, _ = G.pick_layer(cfg, T=T)
+    c = li.cfg
+    say(f"fused gather: config {cfg} T={li.x.shape[0]} seed {li.seed}")
+    dtype, k = c.dtype, c.k
+    Tn = li.x.shape[0]
+    ctx = B.Context(Tn, c.d, c.F, c.E, k, dtype)
+    dev = lambda a: G.to_dev(a, dtype)
+    args = (dev(li.Wg), G.f32_dev(li.bg) if li.bg is not None else None, dev(li.W1), None, dev(li.W2), None)
+    x0 = dev(li.x)
+    x1 = dev(WL.next_step_x(cfg, li.x))
+    out = {}
+    for fused in (True, False):
+        buf = B.LayerBuffers(ctx, G.DEV, with_cache=True)
+        buf.x_packed.fill_(-5.0)
+        y_sync = B.moe_layer_forward(ctx, buf, x0, *args, fuse_gather=fused).clone()
+        torch.cuda.synchronize()
+        R = int(G.to_np(buf.offsets)[-1])
+        h_sync = G.to_np(buf.h_packed)[:R].copy()
+        if fused:
+            assert (G.to_np(buf.x_packed) == -5.0).all()        # never materialised
+        B.moe_layer_forward(ctx, buf, x0, *args, policy=B.Policy(B.REFRESH_ALL), fuse_gather=fused)
+        y_off = B.moe_layer_forward(ctx, buf, x1, *args, policy=B.Policy(B.REFRESH_ALG4, step_t=1, stride_n=2),
+                                    fuse_gather=fused).clone()
+        torch.cuda.synchronize()
+        R1 = int(G.to_np(buf.offsets)[-1])
+        assert R1 == Tn                                          # slot 0 of every token
+        out[fused] = (G.to_np(y_sync), h_sync, G.to_np(y_off), G.to_np(buf.h_packed)[:R1].copy())
+    for a, b_ in zip(out[True], out[False]):
+        np.testing.assert_array_equal(a, b_)
+    if cfg in (1, 2):
+        ref = O.moe_layer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, k)
+        G.assert_close_storage(out[True][0], ref.y, dtype, f"cfg{cfg} fused y")
+
+
 def sampled_layer_check(g, ref_idx_stage, li, k, name, n_rows=96, n_tok=64, seed=0):
     """Full-size check: integer stages in full, FFN rows and output tokens on a sample."""
     c = li.cfg
