@@ -6,8 +6,10 @@
 // pair ids [w*L, (w+1)*L), so "wave-major, then lane order" is ascending pair id and the sort is
 // stable by construction.  Lanes that hold the same expert find each other with six ballots (one
 // per bit of the expert id); the lowest such lane keeps a per-wave, per-expert running count in
-// LDS.  Phase A counts, a scan over (expert, wave) turns the counts into bases, phase B walks the
-// range again and writes perm / inv.  All integer work, no atomics: the result is unique.
+// LDS.  Phase A counts (and remembers each pair's rank inside its wave-and-expert group), a scan
+// over (expert, wave) turns the counts into bases, phase B adds base and rank and writes perm / inv
+// (for ranges too long for registers it walks the range again instead).  All integer work, no
+// atomics: the result is unique.
 //
 // dispatch_gather_kernel: one wavefront per token reads the row once (16 bytes per lane per
 // pass) and stores it to each of its refreshed slots' packed rows; bound by HBM traffic
@@ -70,6 +72,10 @@ __device__ __forceinline__ void load_chunk(const int32_t* __restrict__ expert_id
     }
 }
 
+// MAXC > 0: the wave's whole range fits in MAXC chunks, so the expert ids and the rank of every pair
+// inside its (wave, expert) group stay in registers between the counting pass and the placement:
+// one pass of loads and ballots instead of two.  MAXC == 0: any N, two passes over global memory.
+template <int MAXC>
 __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32_t* __restrict__ expert_idx,
                                                                     const uint8_t* __restrict__ mask, int N, int E,
                                                                     int32_t* __restrict__ counts,
@@ -90,19 +96,48 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
     wave_run[tid / kMaxExperts][tid % kMaxExperts] = 0;   // 1024 threads cover the 16 x 64 table
     __syncthreads();
 
+    constexpr int NC = MAXC > 0 ? MAXC : 1;
+    int ev_keep[NC][kChunk];      // expert id, -1 if not live
+    int rank_keep[NC][kChunk];    // pairs of the same wave and expert before this one
+
     // Both phases walk the range in chunks of kChunk wave-wide steps: all loads of a chunk are
     // issued first (they are independent), then the steps are processed from registers in order.
     // phase A: per-wave, per-expert counts of refreshed pairs
-    for (int c0 = lo; c0 < hi; c0 += kWave * kChunk) {
-        int ev[kChunk];
-        load_chunk(expert_idx, mask, c0, lane, hi, E, ev);
+    if (MAXC > 0) {
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
-            const bool live = ev[u] >= 0;
-            const int e = live ? ev[u] : 0;
-            const uint64_t peers = same_expert_peers(live, e);
-            if (live && (peers & lanemask_lt()) == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
-            wave_sync();
+        for (int c = 0; c < NC; ++c) {
+            const int c0 = lo + c * kWave * kChunk;
+            if (c0 < hi) {                                 // wave-uniform
+                load_chunk(expert_idx, mask, c0, lane, hi, E, ev_keep[c]);
+#pragma unroll
+                for (int u = 0; u < kChunk; ++u) {
+                    const bool live = ev_keep[c][u] >= 0;
+                    const int e = live ? ev_keep[c][u] : 0;
+                    const uint64_t peers = same_expert_peers(live, e);
+                    const int before = __popcll(peers & lanemask_lt());
+                    const int run = wave_run[wave][e];     // every peer reads the same running count ...
+                    rank_keep[c][u] = run + before;
+                    wave_sync();
+                    if (live && before == 0) wave_run[wave][e] = run + __popcll(peers);   // ... then the first updates it
+                    wave_sync();
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kChunk; ++u) { ev_keep[c][u] = -1; rank_keep[c][u] = 0; }
+            }
+        }
+    } else {
+        for (int c0 = lo; c0 < hi; c0 += kWave * kChunk) {
+            int ev[kChunk];
+            load_chunk(expert_idx, mask, c0, lane, hi, E, ev);
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u) {
+                const bool live = ev[u] >= 0;
+                const int e = live ? ev[u] : 0;
+                const uint64_t peers = same_expert_peers(live, e);
+                if (live && (peers & lanemask_lt()) == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
+                wave_sync();
+            }
         }
     }
     __syncthreads();
@@ -129,23 +164,43 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
     const int R = s_off[E];
 
     // phase B: final positions
-    for (int c0 = lo; c0 < hi; c0 += kWave * kChunk) {
-        int ev[kChunk];
-        load_chunk(expert_idx, mask, c0, lane, hi, E, ev);
+    if (MAXC > 0) {
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
-            const int p = c0 + u * kWave + lane;
-            const bool live = ev[u] >= 0;
-            const int e = live ? ev[u] : 0;
-            const uint64_t peers = same_expert_peers(live, e);
-            const int before = __popcll(peers & lanemask_lt());
-            int r = -1;
-            if (live) r = s_off[e] + wave_run[wave][e] + before;
-            wave_sync();
-            if (live && before == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
-            wave_sync();
-            if (live) perm[r] = p;
-            if (p < hi) inv[p] = r;
+        for (int c = 0; c < NC; ++c) {
+            const int c0 = lo + c * kWave * kChunk;
+            if (c0 < hi) {
+#pragma unroll
+                for (int u = 0; u < kChunk; ++u) {
+                    const int p = c0 + u * kWave + lane;
+                    const int e = ev_keep[c][u];
+                    int r = -1;
+                    if (e >= 0) {
+                        r = s_off[e] + wave_run[wave][e] + rank_keep[c][u];
+                        perm[r] = p;
+                    }
+                    if (p < hi) inv[p] = r;
+                }
+            }
+        }
+    } else {
+        for (int c0 = lo; c0 < hi; c0 += kWave * kChunk) {
+            int ev[kChunk];
+            load_chunk(expert_idx, mask, c0, lane, hi, E, ev);
+#pragma unroll
+            for (int u = 0; u < kChunk; ++u) {
+                const int p = c0 + u * kWave + lane;
+                const bool live = ev[u] >= 0;
+                const int e = live ? ev[u] : 0;
+                const uint64_t peers = same_expert_peers(live, e);
+                const int before = __popcll(peers & lanemask_lt());
+                int r = -1;
+                if (live) r = s_off[e] + wave_run[wave][e] + before;
+                wave_sync();
+                if (live && before == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
+                wave_sync();
+                if (live) perm[r] = p;
+                if (p < hi) inv[p] = r;
+            }
         }
     }
     for (int r = R + tid; r < N; r += kIdxThreads) perm[r] = -1;
@@ -180,8 +235,20 @@ hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const u
                            int32_t* inv, hipStream_t stream)
 {
     const int N = T_tok * k;
-    hipLaunchKernelGGL(dispatch_index_kernel, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
-                       offsets, perm, inv);
+    // pairs per wave, rounded up to whole wave-wide steps; up to 4 chunks of them stay in registers
+    const int per_wave = (((N + kIdxWaves - 1) / kIdxWaves) + kWave - 1) / kWave * kWave;
+    if (per_wave <= kWave * kChunk)
+        hipLaunchKernelGGL(dispatch_index_kernel<1>, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
+                           offsets, perm, inv);
+    else if (per_wave <= 2 * kWave * kChunk)
+        hipLaunchKernelGGL(dispatch_index_kernel<2>, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
+                           offsets, perm, inv);
+    else if (per_wave <= 4 * kWave * kChunk)
+        hipLaunchKernelGGL(dispatch_index_kernel<4>, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
+                           offsets, perm, inv);
+    else
+        hipLaunchKernelGGL(dispatch_index_kernel<0>, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
+                           offsets, perm, inv);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || T_tok == 0 || x_packed == nullptr) return err;   // no packed buffer: index only
     const int blocks = (T_tok + 3) / 4;

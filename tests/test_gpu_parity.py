@@ -130,6 +130,10 @@ def test_refresh_mask_bit_exact(T, k):
     (8192, 8, 2, 1152, "bf16", True),
     (17, 3, 3, 64, "f32", True),
     (1, 4, 2, 64, "bf16", False),
+    # pair counts that take each variant of the index kernel (1, 2, 4 register chunks per wave; two passes)
+    (5003, 8, 2, 64, "bf16", True),
+    (12001, 8, 2, 64, "bf16", True),
+    (20480, 16, 2, 64, "bf16", False),
 ])
 def test_dispatch_bit_exact(T, E, k, d, dtype, masked):
     say(f"dispatch T={T} E={E} k={k} d={d} {dtype} masked={masked}")
