@@ -12,7 +12,9 @@
 
 namespace dicemoe {
 
-template <typename T>
+// KK > 0: k == KK, the per-pair scalars (packed row, score, fresh or reused) are read once per token
+// and the k row loads of a 16-byte column slice are issued together; KK == 0: any k, pair by pair.
+template <typename T, int KK>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_packed, const int32_t* __restrict__ inv,
                                                       const float* __restrict__ scores,
                                                       const uint8_t* __restrict__ mask, int T_tok, int d, int k,
@@ -24,34 +26,73 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
     const int lane = lane_id();
     const int nvec = d / V;
     const size_t p0 = static_cast<size_t>(tok) * k;
-    const uint4* hp = reinterpret_cast<const uint4*>(h_packed);
-    uint4* hc = reinterpret_cast<uint4*>(H_cache);
-    uint4* yo = reinterpret_cast<uint4*>(y) + static_cast<size_t>(tok) * nvec;
+    const u32x4_t* hp = reinterpret_cast<const u32x4_t*>(h_packed);
+    u32x4_t* hc = reinterpret_cast<u32x4_t*>(H_cache);
+    u32x4_t* yo = reinterpret_cast<u32x4_t*>(y) + static_cast<size_t>(tok) * nvec;
 
-    for (int c = lane; c < nvec; c += kWave) {
-        float acc[V];
+    if (KK > 0) {
+        constexpr int KN = KK > 0 ? KK : 1;
+        const u32x4_t* src[KN];        // row to read for slot j, nullptr for a refreshed pair without a packed row
+        float sc[KN];
+        bool fresh[KN];
 #pragma unroll
-        for (int t = 0; t < V; ++t) acc[t] = 0.f;
-        for (int j = 0; j < k; ++j) {
+        for (int j = 0; j < KN; ++j) {
             const size_t p = p0 + j;
-            const bool fresh = (mask == nullptr) || mask[p] != 0;
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            float s;
-            if (fresh) {
+            fresh[j] = (mask == nullptr) || mask[p] != 0;
+            if (fresh[j]) {
                 const int r = inv[p];
-                if (r >= 0) v = hp[static_cast<size_t>(r) * nvec + c];
-                s = scores[p];
-                if (hc) hc[p * nvec + c] = v;
+                src[j] = r >= 0 ? hp + static_cast<size_t>(r) * nvec : nullptr;
+                sc[j] = scores[p];
             } else {
-                v = hc[p * nvec + c];
-                s = use_fresh ? scores[p] : S_cache[p];
+                src[j] = hc + p * nvec;
+                sc[j] = use_fresh ? scores[p] : S_cache[p];
             }
-            float f[V];
-            Store<T>::unpack(v, f);
-#pragma unroll
-            for (int t = 0; t < V; ++t) acc[t] = fmaf(s, f[t], acc[t]);
         }
-        yo[c] = Store<T>::pack(acc);
+        for (int c = lane; c < nvec; c += kWave) {
+            u32x4_t v[KN];
+#pragma unroll
+            for (int j = 0; j < KN; ++j) v[j] = src[j] ? src[j][c] : u32x4_t{0u, 0u, 0u, 0u};
+            float acc[V];
+#pragma unroll
+            for (int t = 0; t < V; ++t) acc[t] = 0.f;
+#pragma unroll
+            for (int j = 0; j < KN; ++j) {
+                float f[V];
+                Store<T>::unpack(v[j], f);
+#pragma unroll
+                for (int t = 0; t < V; ++t) acc[t] = fmaf(sc[j], f[t], acc[t]);
+                if (fresh[j] && hc) hc[(p0 + j) * nvec + c] = v[j];
+            }
+            const uint4 packed = Store<T>::pack(acc);
+            yo[c] = u32x4_t{packed.x, packed.y, packed.z, packed.w};
+        }
+    } else {
+        for (int c = lane; c < nvec; c += kWave) {
+            float acc[V];
+#pragma unroll
+            for (int t = 0; t < V; ++t) acc[t] = 0.f;
+            for (int j = 0; j < k; ++j) {
+                const size_t p = p0 + j;
+                const bool is_fresh = (mask == nullptr) || mask[p] != 0;
+                u32x4_t v = u32x4_t{0u, 0u, 0u, 0u};
+                float s;
+                if (is_fresh) {
+                    const int r = inv[p];
+                    if (r >= 0) v = hp[static_cast<size_t>(r) * nvec + c];
+                    s = scores[p];
+                    if (hc) hc[p * nvec + c] = v;
+                } else {
+                    v = hc[p * nvec + c];
+                    s = use_fresh ? scores[p] : S_cache[p];
+                }
+                float f[V];
+                Store<T>::unpack(v, f);
+#pragma unroll
+                for (int t = 0; t < V; ++t) acc[t] = fmaf(s, f[t], acc[t]);
+            }
+            const uint4 packed = Store<T>::pack(acc);
+            yo[c] = u32x4_t{packed.x, packed.y, packed.z, packed.w};
+        }
     }
     if (S_cache && lane < k) {
         const size_t p = p0 + lane;
@@ -59,20 +100,30 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
     }
 }
 
+template <typename T>
+static void launch_combine_t(const void* h_packed, const int32_t* inv, const float* scores, const uint8_t* mask,
+                             int T_tok, int d, int k, void* H_cache, float* S_cache, int use_fresh, void* y,
+                             hipStream_t stream)
+{
+    const int blocks = (T_tok + 3) / 4;
+#define DICEMOE_COMBINE(KK_)                                                                                     \
+    hipLaunchKernelGGL((combine_kernel<T, KK_>), dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(h_packed), \
+                       inv, scores, mask, T_tok, d, k, static_cast<T*>(H_cache), S_cache, use_fresh, static_cast<T*>(y))
+    if (k == 1) DICEMOE_COMBINE(1);
+    else if (k == 2) DICEMOE_COMBINE(2);
+    else if (k == 3) DICEMOE_COMBINE(3);
+    else if (k == 4) DICEMOE_COMBINE(4);
+    else DICEMOE_COMBINE(0);
+#undef DICEMOE_COMBINE
+}
+
 hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, const float* scores,
                           const uint8_t* mask, int T_tok, int d, int k, void* H_cache, float* S_cache,
                           int use_fresh, void* y, hipStream_t stream)
 {
     if (T_tok == 0) return hipSuccess;
-    const int blocks = (T_tok + 3) / 4;
-    if (bf16)
-        hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(blocks), dim3(256), 0, stream,
-                           static_cast<const bf16_t*>(h_packed), inv, scores, mask, T_tok, d, k,
-                           static_cast<bf16_t*>(H_cache), S_cache, use_fresh, static_cast<bf16_t*>(y));
-    else
-        hipLaunchKernelGGL(combine_kernel<float>, dim3(blocks), dim3(256), 0, stream,
-                           static_cast<const float*>(h_packed), inv, scores, mask, T_tok, d, k,
-                           static_cast<float*>(H_cache), S_cache, use_fresh, static_cast<float*>(y));
+    if (bf16) launch_combine_t<bf16_t>(h_packed, inv, scores, mask, T_tok, d, k, H_cache, S_cache, use_fresh, y, stream);
+    else launch_combine_t<float>(h_packed, inv, scores, mask, T_tok, d, k, H_cache, S_cache, use_fresh, y, stream);
     return hipGetLastError();
 }
 

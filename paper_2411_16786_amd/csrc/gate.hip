@@ -131,7 +131,9 @@ __global__ __launch_bounds__(256) void gate_kernel(const T* __restrict__ x, cons
 // its MFMAs.  Accumulator register v of lane l is logits[token 4*(l/16)+v][expert l%16].  The four
 // partial sums meet in LDS and are added in wavefront order (fixed, reproducible); then wavefront w
 // finishes tokens 4w..4w+3 with lane e playing expert e (rank by logit, ties to the lower id).
-template <int NB>
+// U = k-steps per batch and wavefront: the launcher picks it so that one batch covers a wavefront's
+// whole share of the row (a single round trip to memory) whenever that fits in registers.
+template <int NB, int U>
 __global__ __launch_bounds__(256) void gate_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg,
                                                         const float* __restrict__ bg, int T_tok, int d, int E,
                                                         int k, int renorm, float* __restrict__ scores,
@@ -141,7 +143,6 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const bf16_t* __restrict
     typedef __bf16 bf16x8_g __attribute__((ext_vector_type(8)));
     typedef float f32x4_g __attribute__((ext_vector_type(4)));
     constexpr int EP = NB * 16;                  // padded expert count
-    constexpr int U = 8;                         // k-steps per batch and wavefront
     __shared__ float part[4][16][EP];
     __shared__ float zfin[16][EP];
     const int wave = threadIdx.x / kWave;
@@ -230,23 +231,40 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const bf16_t* __restrict
     }
 }
 
+template <int NB>
+static hipError_t launch_gate_mfma_nb(const bf16_t* xb, const bf16_t* wb, const float* bg, int T_tok, int d, int E, int k,
+                                      int renorm, float* scores, int32_t* idx, float* probs, float* logits,
+                                      hipStream_t stream)
+{
+    const int blocks = (T_tok + 15) / 16;
+    const int need = (d / 32 + 3) / 4;           // k-steps per wavefront
+    // registers per lane: 4 * U * (1 + NB) for the operands of a batch
+    constexpr int UMAX = NB == 1 ? 16 : (NB == 2 ? 10 : 6);
+#define DICEMOE_GATE_U(U_)                                                                                          \
+    if (need <= U_ || U_ == UMAX) {                                                                                 \
+        hipLaunchKernelGGL((gate_mfma_kernel<NB, U_>), dim3(blocks), dim3(256), 0, stream, xb, wb, bg, T_tok, d, E, \
+                           k, renorm, scores, idx, probs, logits);                                                  \
+        return hipGetLastError();                                                                                   \
+    }
+    DICEMOE_GATE_U(3)
+    DICEMOE_GATE_U(6)
+    if (UMAX >= 9) { DICEMOE_GATE_U((UMAX >= 9 ? 9 : UMAX)) }
+    if (UMAX >= 10) { DICEMOE_GATE_U((UMAX >= 10 ? 10 : UMAX)) }
+    if (UMAX >= 12) { DICEMOE_GATE_U((UMAX >= 12 ? 12 : UMAX)) }
+    if (UMAX >= 16) { DICEMOE_GATE_U((UMAX >= 16 ? 16 : UMAX)) }
+#undef DICEMOE_GATE_U
+    return hipErrorInvalidValue;                 // not reached: the last case of every NB takes any d
+}
+
 static hipError_t launch_gate_mfma(const void* x, const void* Wg, const float* bg, int T_tok, int d, int E, int k,
                                    int renorm, float* scores, int32_t* idx, float* probs, float* logits,
                                    hipStream_t stream)
 {
-    const int blocks = (T_tok + 15) / 16;
     const bf16_t* xb = static_cast<const bf16_t*>(x);
     const bf16_t* wb = static_cast<const bf16_t*>(Wg);
-    if (E <= 16)
-        hipLaunchKernelGGL(gate_mfma_kernel<1>, dim3(blocks), dim3(256), 0, stream, xb, wb, bg, T_tok, d, E, k, renorm,
-                           scores, idx, probs, logits);
-    else if (E <= 32)
-        hipLaunchKernelGGL(gate_mfma_kernel<2>, dim3(blocks), dim3(256), 0, stream, xb, wb, bg, T_tok, d, E, k, renorm,
-                           scores, idx, probs, logits);
-    else
-        hipLaunchKernelGGL(gate_mfma_kernel<4>, dim3(blocks), dim3(256), 0, stream, xb, wb, bg, T_tok, d, E, k, renorm,
-                           scores, idx, probs, logits);
-    return hipGetLastError();
+    if (E <= 16) return launch_gate_mfma_nb<1>(xb, wb, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream);
+    if (E <= 32) return launch_gate_mfma_nb<2>(xb, wb, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream);
+    return launch_gate_mfma_nb<4>(xb, wb, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream);
 }
 
 template <typename T, int EMAX, int NCH, int TPW>

@@ -259,7 +259,8 @@ def test_expert_ffn_wide_tiles_on_sampled_rows(case):
 
 
 # ----------------------------------------------------------------------------- combine
-@pytest.mark.parametrize("T,k,d,dtype", [(64, 2, 64, "f32"), (333, 3, 128, "bf16"), (4096, 2, 1152, "bf16")])
+@pytest.mark.parametrize("T,k,d,dtype", [(64, 2, 64, "f32"), (333, 3, 128, "bf16"), (4096, 2, 1152, "bf16"),
+                                         (50, 1, 64, "f32"), (100, 6, 192, "bf16"), (77, 4, 64, "bf16")])
 def test_combine_against_oracle_on_the_same_rows(T, k, d, dtype):
     say(f"combine T={T} k={k} d={d} {dtype}")
     r = np.random.Generator(np.random.PCG64(40 + T))
