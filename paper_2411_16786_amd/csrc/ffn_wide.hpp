@@ -24,7 +24,7 @@ __device__ __forceinline__ void wait_lgkmcnt() {
 
 #define DICEMOE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-template <int TM, int TN, int SPREAD, int STAGES, bool GELU, int DIAG>
+template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG>
 __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
@@ -36,16 +36,18 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     constexpr int CH = 8;                          // 16-byte chunks per 64-deep tile row
     constexpr int QA = BM / 32, QB = BN / 32;      // direct-to-LDS loads per wavefront and stage (8 rows each)
     constexpr int QW = QA + QB;
-    constexpr int STAGE = (BM + BN) * 128;         // bytes
+    constexpr int ABYTES = BM * 128, WBYTES = BN * 128;      // one stage of each operand
     constexpr int NFRAG = TM + TN;
     constexpr int NMFMA = TM * TN;
     constexpr int GROUP_M = 8;
     constexpr int REGION = epilogue_region_bytes<TN>();
-    static_assert(4 * REGION <= STAGES * STAGE, "epilogue slabs must fit in the stage buffers");
-    static_assert(STAGES == 2 || STAGES == 3, "ring of two or three stages");
+    static_assert(4 * REGION <= AST * ABYTES + WST * WBYTES, "epilogue slabs must fit in the stage buffers");
+    static_assert((AST == 2 && (WST == 2 || WST == 3)) || (AST == 3 && WST == 3), "ring depths (A, W): (2,2), (2,3), (3,3)");
     static_assert(NMFMA >= NFRAG, "one fragment read per MFMA slot");
     static_assert(SPREAD >= 1 && SPREAD <= 4, "a refill is issued within the four slices before it is needed");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    char* const a_lds = smem;
+    char* const w_lds = smem + AST * ABYTES;
 
     // ---- which tile (bands of GROUP_M row tiles, XCD x takes the x-th eighth of the sequence)
     const int t = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     float bias_reg[(WN + 63) / 64];
     load_bias_columns<WN>(bias ? bias + static_cast<size_t>(e) * N + col_first : nullptr, N - col_first, lane, bias_reg);
 
-    // ---- direct-to-LDS sources.  Load q of the A part fills tile rows 8q .. 8q+7; lane l lands at
+    // ---- direct-to-LDS sources.  Load q of an operand fills tile rows 8q .. 8q+7; lane l lands at
     // LDS slot (row 8q + l/8, l%8) and therefore fetches the chunk that the swizzle assigns to that slot.
     // With a row index, packed row r is read from A row row_index[r] / row_div (the pair id of
     // the packed row divided by k is its token): the dispatch gather folded into the operand load.
@@ -104,27 +106,27 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         asm volatile("" : "+s"(p));
         return p;
     };
-    auto dma = [&](int i, int stage, const char* a_k, const char* w_k) {
-        // i < QA: A part, else W part
+    // load i of a stage: i < QA belongs to the A operand (ring slot sa), the others to W (ring slot sw)
+    auto dma = [&](int i, int sa, int sw, const char* a_k, const char* w_k) {
         if (DIAG & 2) return;
         uint32_t off = goff[i];
         asm volatile("" : "+v"(off));          // keeps the zero extension next to the load (scalar base + 32-bit offset form)
         if (i < QA)
             __builtin_amdgcn_global_load_lds(DICEMOE_GLOBAL_PTR(a_k + off),
-                                             DICEMOE_LDS_PTR(smem + stage * STAGE + (wave * QA + i) * 1024), 16, 0, 0);
+                                             DICEMOE_LDS_PTR(a_lds + sa * ABYTES + (wave * QA + i) * 1024), 16, 0, 0);
         else
             __builtin_amdgcn_global_load_lds(DICEMOE_GLOBAL_PTR(w_k + off),
-                                             DICEMOE_LDS_PTR(smem + stage * STAGE + BM * 128 + (wave * QB + (i - QA)) * 1024), 16, 0, 0);
+                                             DICEMOE_LDS_PTR(w_lds + sw * WBYTES + (wave * QB + (i - QA)) * 1024), 16, 0, 0);
     };
 
-    // ---- fragment offsets inside a stage: 32-row blocks are 4 KiB apart, k slices differ in the chunk
+    // ---- fragment offsets inside an operand's stage: 32-row blocks are 4 KiB apart, k slices differ in the chunk
     int a_off[4], b_off[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         const int chunk = kk * 2 + (lane >> 5);
         const int ra = wm * WM + (lane & 31), rb = wn * WN + (lane & 31);
         a_off[kk] = (ra * CH + (chunk ^ chunk_swizzle<CH>(ra))) * 16;
-        b_off[kk] = BM * 128 + (rb * CH + (chunk ^ chunk_swizzle<CH>(rb))) * 16;
+        b_off[kk] = (rb * CH + (chunk ^ chunk_swizzle<CH>(rb))) * 16;
     }
 
     f32x16_v acc[TM][TN];
@@ -136,9 +138,9 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     bf16x8_v fr[2][NFRAG];                           // [set][A fragments 0..TM-1, then W fragments]
-    auto read_frag = [&](int set, int f, const char* st, int kk) {
+    auto read_frag = [&](int set, int f, const char* sta, const char* stw, int kk) {
         if (DIAG & 4) return;
-        const char* p = f < TM ? st + a_off[kk] + f * 4096 : st + b_off[kk] + (f - TM) * 4096;
+        const char* p = f < TM ? sta + a_off[kk] + f * 4096 : stw + b_off[kk] + (f - TM) * 4096;
         const u32x4_v v = *reinterpret_cast<const u32x4_v*>(p);
         fr[set][f] = *reinterpret_cast<const bf16x8_v*>(&v);
     };
@@ -147,28 +149,32 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][TM + j], fr[set][i], acc[i][j], 0, 0, 0);
     };
 
-    const int nk = K / 64;                          // the launcher guarantees nk >= 4 when STAGES == 3
+    const int nk = K / 64;                          // the launcher guarantees nk >= 4 for a three-deep ring
     // ---- prologue: every stage in flight, first fragments in registers.  The W parts go first: they
     // do not depend on the row index, whose load is still in flight when a gathering kernel gets here.
 #pragma unroll
-    for (int part = 0; part < 2; ++part) {
+    for (int s = 0; s < WST; ++s) {
+        if (s < nk) {
+            const char* w_k = step_base(w_base, s);
 #pragma unroll
-        for (int s = 0; s < STAGES; ++s) {
-            if (s < nk) {
-                const char* a_k = step_base(a_base, s);
-                const char* w_k = step_base(w_base, s);
+            for (int i = QA; i < QW; ++i) dma(i, 0, s, nullptr, w_k);
+        }
+    }
 #pragma unroll
-                for (int i = (part == 0 ? QA : 0); i < (part == 0 ? QW : QA); ++i) dma(i, s, a_k, w_k);
-            }
+    for (int s = 0; s < AST; ++s) {
+        if (s < nk) {
+            const char* a_k = step_base(a_base, s);
+#pragma unroll
+            for (int i = 0; i < QA; ++i) dma(i, s, 0, a_k, nullptr);
         }
     }
     // loads return in order: stage 0 is complete once its A part is, i.e. when at most the A parts of
     // the younger stages are outstanding
-    if (nk >= STAGES) wait_vmcnt<(STAGES - 1) * QA>();
+    if (nk >= WST) wait_vmcnt<(AST - 1) * QA>();
     else wait_vmcnt<0>();
     block_barrier();
 #pragma unroll
-    for (int f = 0; f < NFRAG; ++f) read_frag(0, f, smem, 0);
+    for (int f = 0; f < NFRAG; ++f) read_frag(0, f, a_lds, w_lds, 0);
     if (DIAG & 4) {
 #pragma unroll
         for (int f = 0; f < NFRAG; ++f) {
@@ -177,30 +183,35 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         }
     }
 
-    // One 64-deep step kt, whose stage sits in ring buffer s_cur.
-    //   NEXT:   step kt+1 exists (barrier, first fragments of the next stage).
-    //   PEND:   three stages only -- the loads of stage kt+2 are in flight behind those of stage kt+1, so
-    //           the wait before the barrier lets the youngest QW loads stay outstanding (loads return
-    //           in order).
-    //   REFILL: step kt+STAGES exists; its stage is requested into the buffer this step drains.
-    //   CARRY:  the previous step started a refill whose later parts are issued here.
-    // A refill's QW loads are issued in SPREAD parts, one slice each, so that the four wavefronts do
-    // not push more loads at the texture path than it takes per slice (a full queue stalls MFMA issue).
+    // One 64-deep step kt; its A stage sits in ring slot sa, its W stage in ring slot sw (the rings may
+    // differ in depth: the W operand streams from HBM once and gains most from a third stage, the
+    // activations come from cache).  After the barrier of this step the slots are drained and take the
+    // stages kt+AST (A) and kt+WST (W): the "refill", A loads first, issued in SPREAD parts, one slice
+    // each (part 0 beside the last slice, the others beside the first slices of step kt+1), so that the
+    // four wavefronts do not push more loads at the texture path than it takes per slice (a full queue
+    // stalls MFMA issue).
+    //   NEXT:        step kt+1 exists (barrier, first fragments of the next stage)
+    //   PEND:        number of this wavefront's loads that may still be in flight at the barrier: those
+    //                issued after the loads of stage kt+1 (loads return in order)
+    //   REFA, REFW:  the refill of this step has an A part / a W part
+    //   CARA, CARW:  the previous step's refill had an A part / a W part (its later parts are issued here)
     constexpr int PART = (QW + SPREAD - 1) / SPREAD;
-    auto step = [&](int kt, int s_cur, auto next_tag, auto pend_tag, auto refill_tag, auto carry_tag, auto first_tag) {
-        constexpr bool FIRST = decltype(first_tag)::value;     // step 0: the prologue issued the A parts last
+    auto step = [&](int kt, int sa, int sw, auto next_tag, auto pend_tag, auto refa_tag, auto refw_tag, auto cara_tag,
+                    auto carw_tag) {
         constexpr bool NEXT = decltype(next_tag)::value;
-        constexpr bool PEND = decltype(pend_tag)::value;
-        constexpr bool REFILL = decltype(refill_tag)::value;
-        constexpr bool CARRY = decltype(carry_tag)::value;
-        const int s_nxt = (s_cur + 1 == STAGES) ? 0 : s_cur + 1;
-        const int s_prev = (s_cur == 0) ? STAGES - 1 : s_cur - 1;
-        const char* cur = smem + s_cur * STAGE;
-        const char* nxt = smem + s_nxt * STAGE;
-        const char* a_carry = step_base(a_base, kt + STAGES - 1);   // the refill in flight fills the previous step's buffer
-        const char* w_carry = step_base(w_base, kt + STAGES - 1);
-        const char* a_refill = step_base(a_base, kt + STAGES);
-        const char* w_refill = step_base(w_base, kt + STAGES);
+        constexpr int PEND = decltype(pend_tag)::value;
+        constexpr bool REFA = decltype(refa_tag)::value, REFW = decltype(refw_tag)::value;
+        constexpr bool CARA = decltype(cara_tag)::value, CARW = decltype(carw_tag)::value;
+        const int sa_nxt = (sa + 1 == AST) ? 0 : sa + 1, sw_nxt = (sw + 1 == WST) ? 0 : sw + 1;
+        const int sa_prev = (sa == 0) ? AST - 1 : sa - 1, sw_prev = (sw == 0) ? WST - 1 : sw - 1;
+        const char* cur_a = a_lds + sa * ABYTES;
+        const char* cur_w = w_lds + sw * WBYTES;
+        const char* nxt_a = a_lds + sa_nxt * ABYTES;
+        const char* nxt_w = w_lds + sw_nxt * WBYTES;
+        const char* a_carry = step_base(a_base, kt - 1 + AST);      // the refill in flight fills the previous step's slots
+        const char* w_carry = step_base(w_base, kt - 1 + WST);
+        const char* a_refill = step_base(a_base, kt + AST);
+        const char* w_refill = step_base(w_base, kt + WST);
 #pragma unroll
         for (int kk = 0; kk < 3; ++kk) {
             const int set = kk & 1;
@@ -209,12 +220,11 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
             for (int m = 0; m < NMFMA; ++m) {
                 mfma(set, m);
                 DICEMOE_SCHED_FENCE();
-                if (m < NFRAG) { read_frag(set ^ 1, m, cur, kk + 1); DICEMOE_SCHED_FENCE(); }
-                if (CARRY && kk + 1 < SPREAD) {
+                if (m < NFRAG) { read_frag(set ^ 1, m, cur_a, cur_w, kk + 1); DICEMOE_SCHED_FENCE(); }
+                if ((CARA || CARW) && kk + 1 < SPREAD) {
 #pragma unroll
                     for (int i = (kk + 1) * PART + m; i < (kk + 2) * PART && i < QW; i += NMFMA) {
-                        dma(i, s_prev, a_carry, w_carry);
-                        DICEMOE_SCHED_FENCE();
+                        if (i < QA ? CARA : CARW) { dma(i, sa_prev, sw_prev, a_carry, w_carry); DICEMOE_SCHED_FENCE(); }
                     }
                 }
             }
@@ -223,7 +233,7 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         DICEMOE_SCHED_FENCE();
         if (NEXT) {
             wait_lgkmcnt<0>();                      // every fragment of this stage has been read
-            wait_vmcnt<PEND ? (FIRST ? QA : QW) : 0>();   // my loads of the next stage have landed
+            wait_vmcnt<PEND>();                     // my loads of the next stage have landed
             block_barrier();
         }
         DICEMOE_SCHED_FENCE();
@@ -231,36 +241,52 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         for (int m = 0; m < NMFMA; ++m) {
             mfma(1, m);
             DICEMOE_SCHED_FENCE();
-            if (NEXT && m < NFRAG) { read_frag(0, m, nxt, 0); DICEMOE_SCHED_FENCE(); }
-            if (REFILL) {
+            if (NEXT && m < NFRAG) { read_frag(0, m, nxt_a, nxt_w, 0); DICEMOE_SCHED_FENCE(); }
+            if (REFA || REFW) {
 #pragma unroll
-                for (int i = m; i < PART && i < QW; i += NMFMA) { dma(i, s_cur, a_refill, w_refill); DICEMOE_SCHED_FENCE(); }
+                for (int i = m; i < PART && i < QW; i += NMFMA) {
+                    if (i < QA ? REFA : REFW) { dma(i, sa, sw, a_refill, w_refill); DICEMOE_SCHED_FENCE(); }
+                }
             }
         }
     };
     const std::true_type yes{};
     const std::false_type no{};
-    int s_cur = 0;
-    auto advance = [&]() { s_cur = (s_cur + 1 == STAGES) ? 0 : s_cur + 1; };
-    if (STAGES == 2) {
+    const std::integral_constant<int, 0> p0{};
+    int sa = 0, sw = 0;
+    auto advance = [&]() { sa = (sa + 1 == AST) ? 0 : sa + 1; sw = (sw + 1 == WST) ? 0 : sw + 1; };
+    // Which loads are younger than those of stage kt+1 at the barrier of step kt follows from the issue
+    // order: prologue W0.. then A0..; refill of step j: A(j+AST) then W(j+WST).
+    if (AST == 2 && WST == 2) {
         if (nk == 1) {
-            step(0, 0, no, no, no, no, yes);
+            step(0, 0, 0, no, p0, no, no, no, no);
         } else {
-            if (nk > 2) step(0, 0, yes, no, yes, no, yes); else step(0, 0, yes, no, no, no, yes);
+            if (nk > 2) step(0, 0, 0, yes, p0, yes, yes, no, no); else step(0, 0, 0, yes, p0, no, no, no, no);
             advance();
             int kt = 1;
-            for (; kt + 2 < nk; ++kt) { step(kt, s_cur, yes, no, yes, yes, no); advance(); }
-            if (nk > 2) { step(kt, s_cur, yes, no, no, yes, no); advance(); ++kt; }
-            step(kt, s_cur, no, no, no, no, no);
+            for (; kt + 2 < nk; ++kt) { step(kt, sa, sw, yes, p0, yes, yes, yes, yes); advance(); }
+            if (nk > 2) { step(kt, sa, sw, yes, p0, no, no, yes, yes); advance(); ++kt; }
+            step(kt, sa, sw, no, p0, no, no, no, no);
         }
-    } else {
-        step(0, 0, yes, yes, yes, no, yes);
+    } else if (AST == 2 && WST == 3) {
+        const std::integral_constant<int, QB> pw{};      // the W part of the previous step's refill
+        step(0, 0, 0, yes, p0, yes, yes, no, no);
         advance();
         int kt = 1;
-        for (; kt + 3 < nk; ++kt) { step(kt, s_cur, yes, yes, yes, yes, no); advance(); }
-        step(kt, s_cur, yes, yes, no, yes, no); advance(); ++kt;      // kt = nk-3
-        step(kt, s_cur, yes, no, no, no, no); advance(); ++kt;        // kt = nk-2
-        step(kt, s_cur, no, no, no, no, no);                          // kt = nk-1
+        for (; kt + 3 < nk; ++kt) { step(kt, sa, sw, yes, pw, yes, yes, yes, yes); advance(); }
+        step(kt, sa, sw, yes, pw, yes, no, yes, yes); advance(); ++kt;      // kt = nk-3: A(nk-1) is the last refill
+        step(kt, sa, sw, yes, p0, no, no, yes, no); advance(); ++kt;        // kt = nk-2
+        step(kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
+    } else {
+        const std::integral_constant<int, QA> pa{};      // step 0: the prologue issued the A parts last
+        const std::integral_constant<int, QW> pq{};      // the previous step's whole refill
+        step(0, 0, 0, yes, pa, yes, yes, no, no);
+        advance();
+        int kt = 1;
+        for (; kt + 3 < nk; ++kt) { step(kt, sa, sw, yes, pq, yes, yes, yes, yes); advance(); }
+        step(kt, sa, sw, yes, pq, no, no, yes, yes); advance(); ++kt;       // kt = nk-3
+        step(kt, sa, sw, yes, p0, no, no, no, no); advance(); ++kt;         // kt = nk-2
+        step(kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
     }
 
     // ---- epilogue: the stage buffers are free once every wavefront is past its last fragment read
@@ -286,16 +312,16 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
         store_slab<TN, GELU>(acc[i], region, bias_lds, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
 }
 
-template <int TM, int TN, int SPREAD, int STAGES, bool GELU, int DIAG = 0>
+template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG = 0>
 static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
                                         int row_div = 1)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
-    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, STAGES, GELU, DIAG>;
-    constexpr int smem = STAGES * (BM + BN) * 128;
-    if (STAGES == 3 && K < 4 * 64) return hipErrorInvalidValue;      // the three-stage loop is written for at least four steps
+    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, AST, WST, GELU, DIAG>;
+    constexpr int smem = (AST * BM + WST * BN) * 128;
+    if (WST == 3 && K < 4 * 64) return hipErrorInvalidValue;      // the three-deep loops are written for at least four steps
     static bool configured = false;
     if (!configured) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
