@@ -196,6 +196,8 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     //   REFA, REFW:  the refill of this step has an A part / a W part
     //   CARA, CARW:  the previous step's refill had an A part / a W part (its later parts are issued here)
     constexpr int PART = (QW + SPREAD - 1) / SPREAD;
+    constexpr int PER = (PART + NMFMA - 1) / NMFMA;     // loads per MFMA slot; issued in index order, A before W,
+                                                        // which is what the PEND counts rely on
     auto step = [&](int kt, int sa, int sw, auto next_tag, auto pend_tag, auto refa_tag, auto refw_tag, auto cara_tag,
                     auto carw_tag) {
         constexpr bool NEXT = decltype(next_tag)::value;
@@ -223,8 +225,12 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
                 if (m < NFRAG) { read_frag(set ^ 1, m, cur_a, cur_w, kk + 1); DICEMOE_SCHED_FENCE(); }
                 if ((CARA || CARW) && kk + 1 < SPREAD) {
 #pragma unroll
-                    for (int i = (kk + 1) * PART + m; i < (kk + 2) * PART && i < QW; i += NMFMA) {
-                        if (i < QA ? CARA : CARW) { dma(i, sa_prev, sw_prev, a_carry, w_carry); DICEMOE_SCHED_FENCE(); }
+                    for (int j = 0; j < PER; ++j) {
+                        const int i = (kk + 1) * PART + m * PER + j;
+                        if (m * PER + j < PART && i < QW && (i < QA ? CARA : CARW)) {
+                            dma(i, sa_prev, sw_prev, a_carry, w_carry);
+                            DICEMOE_SCHED_FENCE();
+                        }
                     }
                 }
             }
@@ -244,8 +250,9 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
             if (NEXT && m < NFRAG) { read_frag(0, m, nxt_a, nxt_w, 0); DICEMOE_SCHED_FENCE(); }
             if (REFA || REFW) {
 #pragma unroll
-                for (int i = m; i < PART && i < QW; i += NMFMA) {
-                    if (i < QA ? REFA : REFW) { dma(i, sa, sw, a_refill, w_refill); DICEMOE_SCHED_FENCE(); }
+                for (int j = 0; j < PER; ++j) {
+                    const int i = m * PER + j;
+                    if (i < PART && i < QW && (i < QA ? REFA : REFW)) { dma(i, sa, sw, a_refill, w_refill); DICEMOE_SCHED_FENCE(); }
                 }
             }
         }
