@@ -158,10 +158,10 @@ def main():
         for line in open(tpath):
             if line.startswith("ffn_traffic_bytes_per_call:"):
                 traffic = int(line.split(":")[1].split()[0])
-    roofline = {"kernel": "ffn_gemm_bf16 (GEMM1 + GEMM2 of one moe_expert_ffn call)", "bound": "mfma",
+    roofline = {"kernel": "ffn_gemm_bf16_wide_kernel (GEMM1 + GEMM2 of one moe_expert_ffn_rows call)", "bound": "mfma",
                 "achieved": round(ffn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(ffn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-                "traffic_note": "HBM-side bytes per moe_expert_ffn call from profiles/bench_xl28_hbm_traffic.txt"}
+                "traffic_note": "HBM-side bytes per moe_expert_ffn_rows call from profiles/bench_xl28_hbm_traffic.txt"}
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
