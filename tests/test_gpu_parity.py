@@ -92,7 +92,8 @@ def gpu_mask(ctx, s_dev, policy):
     return G.to_np(mask), int(n.item())
 
 
-@pytest.mark.parametrize("T,k", [(1, 2), (63, 2), (1024, 2), (1025, 2), (2049, 3), (8192, 2), (5000, 1)])
+@pytest.mark.parametrize("T,k", [(1, 2), (63, 2), (1024, 2), (1025, 2), (2049, 3), (8192, 2), (5000, 1),
+                                 (16384, 2), (16385, 2), (20011, 2)])
 def test_refresh_mask_bit_exact(T, k):
     say(f"refresh mask T={T} k={k}")
     r = np.random.Generator(np.random.PCG64(100 + T))
