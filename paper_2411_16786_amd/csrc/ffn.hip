@@ -188,9 +188,11 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
     char* region = lds + wave * REGION;
     float* bias_lds = reinterpret_cast<float*>(region + slab_bytes<TN>());
     stage_bias<WN>(bias_reg, bias_lds, lane);
+    float4 bias_groups[TN][4];
+    read_bias_groups<TN>(bias_lds, lane, bias_groups);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-        store_slab<TN, GELU>(acc[i], region, bias_lds, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
+        store_slab<TN, GELU>(acc[i], region, bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
 }
 
 // float path (small workloads): 64x64 tile, depth 16, each thread a 4x4 block, plain FMAs in a

@@ -135,38 +135,53 @@ __device__ __forceinline__ void stage_bias(const float (&reg)[(WN + 63) / 64], f
 template <int TN> constexpr int slab_bytes() { return 32 * (TN * 32 * 2 + 16); }
 template <int TN> constexpr int epilogue_region_bytes() { return slab_bytes<TN>() + TN * 32 * 4; }
 
+// the wavefront's bias values in the layout the groups use them: bb[j][g] = columns j*32 + 8g + 4h .. +3
+template <int TN>
+__device__ __forceinline__ void read_bias_groups(const float* bias_lds, int lane, float4 (&bb)[TN][4])
+{
+    const int h = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bb[j][g] = *reinterpret_cast<const float4*>(bias_lds + j * 32 + 8 * g + 4 * h);
+}
+
 template <int TN, bool GELU>
-__device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* region, const float* bias_lds,
+__device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* region, const float4 (&bb)[TN][4],
                                            bf16_t* __restrict__ C, int N, int row_first, int row_end, int col_first,
                                            int lane)
 {
     constexpr int WN = TN * 32;
     constexpr int PITCH = WN * 2 + 16;            // bytes; keeps 16-byte alignment, staggers banks
     constexpr int CPR = WN / 8;                   // 16-byte chunks per slab row
+    constexpr int NP = 32 * CPR / 64;             // 16-byte pieces per lane (32 * CPR = 128 TN: a whole number of wavefronts)
     const int m_local = lane & 31, h = lane >> 5;
+    // phase 1: arithmetic and parking, no LDS read in between (nothing to wait for)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int nl = j * 32 + 8 * g + 4 * h;
-            const float4 bb = *reinterpret_cast<const float4*>(bias_lds + nl);
-            float v0 = half[j][4 * g] + bb.x, v1 = half[j][4 * g + 1] + bb.y;
-            float v2 = half[j][4 * g + 2] + bb.z, v3 = half[j][4 * g + 3] + bb.w;
+            float v0 = half[j][4 * g] + bb[j][g].x, v1 = half[j][4 * g + 1] + bb[j][g].y;
+            float v2 = half[j][4 * g + 2] + bb[j][g].z, v3 = half[j][4 * g + 3] + bb[j][g].w;
             if (GELU) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
             uint2 packed = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
             *reinterpret_cast<uint2*>(region + m_local * PITCH + nl * 2) = packed;
         }
     __builtin_amdgcn_wave_barrier();
+    // phase 2: all row-contiguous pieces of the slab in one batch of LDS reads, then the stores
+    u32x4_v piece[NP];
 #pragma unroll
-    for (int p = 0; p < (32 * CPR + 63) / 64; ++p) {
+    for (int p = 0; p < NP; ++p) {
         const int idx = lane + 64 * p;
-        const int row = idx / CPR, chunk = idx % CPR;
-        if (idx < 32 * CPR) {
-            const u32x4_v v = *reinterpret_cast<const u32x4_v*>(region + row * PITCH + chunk * 16);
-            const int r = row_first + row;
-            const int n = col_first + chunk * 8;
-            if (r < row_end && n < N) *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(r) * N + n) = v;
-        }
+        piece[p] = *reinterpret_cast<const u32x4_v*>(region + (idx / CPR) * PITCH + (idx % CPR) * 16);
+    }
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int idx = lane + 64 * p;
+        const int r = row_first + idx / CPR;
+        const int n = col_first + (idx % CPR) * 8;
+        if (r < row_end && n < N) *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(r) * N + n) = piece[p];
     }
     __builtin_amdgcn_wave_barrier();
 }

@@ -24,8 +24,11 @@ __device__ __forceinline__ void wait_lgkmcnt() {
 
 #define DICEMOE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// workgroups per compute unit that the LDS footprint allows (the register budget follows from it)
+constexpr int wide_occupancy(int tm, int tn, int ast, int wst) { return (ast * tm + wst * tn) * 64 * 128 <= 80 * 1024 ? 2 : 1; }
+
 template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG>
-__global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
+__global__ __launch_bounds__(256, wide_occupancy(TM, TN, AST, WST)) void ffn_gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
     const int32_t* __restrict__ seg_expert, int n_seg, int n_tiles_n, int m_tiles_max,
@@ -314,9 +317,11 @@ __global__ __launch_bounds__(256, 1) void ffn_gemm_bf16_wide_kernel(
     char* region = smem + wave * REGION;
     float* bias_lds = reinterpret_cast<float*>(region + slab_bytes<TN>());
     stage_bias<WN>(bias_reg, bias_lds, lane);
+    float4 bias_groups[TN][4];
+    read_bias_groups<TN>(bias_lds, lane, bias_groups);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-        store_slab<TN, GELU>(acc[i], region, bias_lds, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
+        store_slab<TN, GELU>(acc[i], region, bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
 }
 
 template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG = 0>
