@@ -222,6 +222,12 @@ WIDE_FFN_CASES = [
     ("xl-4096-rows", [695, 306, 602, 446, 673, 350, 560, 464], 1152, 4608),       # 128x192 x2 / three stages
     ("xl-700-rows", [3, 250, 0, 129, 64, 1, 192, 61], 1152, 4608),                # three stages / 128x128
     ("column-tails", [700, 0, 1033, 515, 390, 462], 1088, 1600),                  # widths not multiples of 192
+    # short reductions in the first GEMM: one, two, three and four 64-deep steps (pipeline prologue / tail paths)
+    ("k-64", [900, 411, 1200, 777], 64, 1536),
+    ("k-128", [900, 411, 1200, 777], 128, 1536),
+    ("k-192", [900, 411, 1200, 777], 192, 1536),
+    ("k-256", [900, 411, 1200, 777], 256, 1536),
+    ("k-256-few-rows", [90, 41, 300, 77], 256, 4608),                             # three stages at four steps
 ]
 
 
