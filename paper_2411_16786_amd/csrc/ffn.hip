@@ -25,7 +25,7 @@ namespace dicemoe {
 // next tile's global loads are in flight during the MFMAs), so a workgroup needs only (BM+BN)*128
 // bytes of LDS and two or three workgroups share a compute unit and hide each other's barriers,
 // LDS stores and epilogues.
-template <int BM, int BN, int OCC, bool XCD, bool PF, bool GELU>
+template <int BM, int BN, int OCC, bool XCD, bool GELU>
 __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* __restrict__ A,
                                                                  const bf16_t* __restrict__ W,
                                                                  const float* __restrict__ bias,
@@ -134,55 +134,27 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
 #pragma unroll
             for (int p = 0; p < B_PASSES; ++p) b_reg[p] = b_src[p][koff];
         }
-        if (PF) {
-            // all fragments of the step first (one exposed LDS latency per step instead of four),
-            // then hand the buffer back, then the MFMAs: they overlap the next step's LDS stores
-            bf16x8_v af[BK / 16][TM], bfr[BK / 16][TN];
 #pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8_v af[TM], bfr[TN];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    const u32x4_v v = As[a_off[kk] + i * 32 * CH];
-                    af[kk][i] = *reinterpret_cast<const bf16x8_v*>(&v);
-                }
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const u32x4_v v = Bs[b_off[kk] + j * 32 * CH];
-                    bfr[kk][j] = *reinterpret_cast<const bf16x8_v*>(&v);
-                }
+            for (int i = 0; i < TM; ++i) {
+                const u32x4_v v = As[a_off[kk] + i * 32 * CH];
+                af[i] = *reinterpret_cast<const bf16x8_v*>(&v);
             }
-            __syncthreads();
 #pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
-        } else {
-#pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
-                bf16x8_v af[TM], bfr[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    const u32x4_v v = As[a_off[kk] + i * 32 * CH];
-                    af[i] = *reinterpret_cast<const bf16x8_v*>(&v);
-                }
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const u32x4_v v = Bs[b_off[kk] + j * 32 * CH];
-                    bfr[j] = *reinterpret_cast<const bf16x8_v*>(&v);
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)     // operands swapped: see store_slab
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j) {
+                const u32x4_v v = Bs[b_off[kk] + j * 32 * CH];
+                bfr[j] = *reinterpret_cast<const bf16x8_v*>(&v);
             }
-            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)     // operands swapped: see store_slab
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
+        __syncthreads();
     }
-    if (PF) __syncthreads();                     // the slabs below reuse the tile buffer
 
     // epilogue: the tile buffer is free (barrier above); every wavefront uses its own slab region
     char* region = lds + wave * REGION;
@@ -266,7 +238,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
     }
 }
 
-template <int BM, int BN, int OCC, bool XCD, bool PF, bool GELU>
+template <int BM, int BN, int OCC, bool XCD, bool GELU>
 static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                    const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
                                    hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1)
@@ -274,7 +246,7 @@ static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bi
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
     const int bands = (m_tiles + 7) / 8;
-    hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, OCC, XCD, PF, GELU>), dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n),
+    hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, OCC, XCD, GELU>), dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n),
                        dim3(256), 0, stream, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias,
                        static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index,
                        row_div);
@@ -330,7 +302,7 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
         return launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
     if (fits_192 && tiles(128, 192) * 2 >= kComputeUnits)
         return launch_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
-    return launch_gemm_bf16<128, 128, 3, true, false, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
+    return launch_gemm_bf16<128, 128, 3, true, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
                                                            row_div);
 }
 
