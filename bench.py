@@ -38,6 +38,9 @@ def main():
                          "25/50/75/100 %% and report it under 'conditional_refresh'")
     ap.add_argument("--packed-dispatch", action="store_true",
                     help="materialise x_packed in moe_dispatch instead of gathering rows in the FFN's operand load")
+    ap.add_argument("--n-shared", type=int, default=0,
+                    help="add this many shared experts (always-fresh dense FFNs; DiT-MoE carries 2) to every layer; "
+                         "the headline workload has none")
     ap.add_argument("--eager", action="store_true", help="launch from Python every step instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -56,13 +59,14 @@ def main():
     c = WL.CONFIGS[3]
     n_layers = args.layers or c.layers
     T, d, E, k, F = c.T, c.d, c.E, c.k, c.F
-    N = T * k
+    n_shared = args.n_shared
+    N = T * (k + n_shared)          # (token, slot) pairs: k routed slots and one per shared expert
 
     # ---- inputs: seeded on the host, uploaded once
     t_setup = time.time()
     with ThreadPoolExecutor(max_workers=8) as pool:
-        host_layers = list(pool.map(lambda l: WL.make_layer(3, layer=l), range(n_layers)))
-    ctx = B.Context(T, d, F, E, k, "bf16")
+        host_layers = list(pool.map(lambda l: WL.make_layer(3, layer=l, n_shared=n_shared), range(n_layers)))
+    ctx = B.Context(T, d, F, E, k, "bf16", n_shared=n_shared)
     workspace = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
     up = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(dev)
     layers = []
@@ -140,9 +144,9 @@ def main():
     avg = {s: float(np.mean(v)) for s, v in stage_ms.items()}
     b = 2
     alg_bytes = {
-        "gate": T * d * b + E * d * b + T * k * 8,
+        "gate": T * d * b + E * d * b + N * 8,
         "dispatch": 16 * N,          # index outputs only; the row gather rides in the FFN's operand load
-        "combine": N * d * b + T * d * b + T * k * 9,
+        "combine": N * d * b + T * d * b + N * 9,
     }
     ffn_flops = 4.0 * N * d * F
     ffn_tflops = ffn_flops / (avg["expert_ffn"] * 1e-3) / 1e12
@@ -205,7 +209,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O
         t1 = time.perf_counter()
-        refs = [O.moe_layer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, k) for li in cpu_layers]
+        refs = [O.moe_layer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, k, n_shared=n_shared) for li in cpu_layers]
         cpu_s = time.perf_counter() - t1
         # the same layers through the HIP path (the buffers still hold the last timed pass): a live
         # parity check of exactly the code that was benchmarked
@@ -217,11 +221,16 @@ def main():
             zs = -np.sort(-ref.z, axis=1)
             safe = np.min(zs[:, :k] - zs[:, 1:k + 1], axis=1) > 1e-4
             assert safe.mean() > 0.999
-            assert np.array_equal(L["buf"].expert_idx.cpu().numpy()[safe], ref.idx[safe]), "routing differs from the oracle"
-            if safe.all():
+            assert np.array_equal(L["buf"].expert_idx.cpu().numpy()[safe, :k], ref.idx[safe]), "routing differs from the oracle"
+            if safe.all() and n_shared == 0:
                 assert np.array_equal(L["buf"].perm.cpu().numpy(), ref.perm), "permutation differs from the oracle"
             rel = float(np.linalg.norm(got[safe] - ref.y[safe]) / np.linalg.norm(ref.y[safe]))
-            assert rel <= 1e-2 and np.abs(got[safe] - ref.y[safe]).max() <= 2e-2, "bench output differs from the oracle"
+            # max-abs 2e-2 is fit to |y| up to about 2; ungated shared experts push |y| past 4, where one
+            # bf16 rounding of the output alone costs 1.6e-2, so with them the bound grows with max|y|
+            abs_tol = 2e-2 * (max(1.0, float(np.abs(ref.y).max()) / 2.0) if n_shared else 1.0)
+            worst_abs = float(np.abs(got[safe] - ref.y[safe]).max())
+            assert rel <= 1e-2 and worst_abs <= abs_tol, \
+                f"bench output differs from the oracle: rel-L2 {rel:.3e}, max-abs {worst_abs:.3e} (bound {abs_tol:.3e})"
             worst = max(worst, rel)
         n_lay = len(cpu_layers)
         cpu_baseline = {"value": round(T * n_lay / cpu_s, 2), "unit": "tokens/s (token passes through one MoE layer)",
@@ -238,7 +247,8 @@ def main():
         "ms_per_layer": round(ms_per_step / n_layers, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[2]: DiT-MoE-XL-shaped layer x 28 (T=4096, d=1152, E=8, top-2, F=4608)",
+        "config": {"workload": "configs[2]: DiT-MoE-XL-shaped layer x 28 (T=4096, d=1152, E=8, top-2, F=4608)"
+                               + (f" + {n_shared} shared experts per layer" if n_shared else ""),
                    "layers": n_layers, "tokens": T, "launch": "eager" if graph is None else "hipGraph replay",
                    "refresh": "full (synchronous layer)"},
         "roofline": roofline,

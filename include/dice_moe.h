@@ -62,6 +62,13 @@ typedef struct {
     int32_t renorm_topk; /* 0: scores are the softmax over all E experts taken at the selected
                             ones (default; the paper only says "router scores");
                             1: additionally divided by their sum over the k selected */
+    int32_t n_shared;    /* shared experts of the DiT-MoE layer (model description: experts that every
+                            token uses, always fresh, unscaled).  They are carried as n_shared extra
+                            slots per token behind the k routed ones: slot k+s of every token goes to
+                            expert id E+s with score 1 and is refreshed under every policy.  All
+                            per-pair arrays then have k + n_shared columns and the expert weights
+                            hold E + n_shared experts (shared ones last); E + n_shared <= 64.
+                            0 = routed experts only. */
 } moe_shape;
 
 /* Which (token, slot) pairs are recomputed ("transmitted") in this step; the others reuse the
@@ -99,6 +106,14 @@ size_t moe_workspace_bytes(const moe_ctx* ctx);
 const char* moe_last_error(const moe_ctx* ctx);
 /* Name of a status code. */
 const char* moe_status_string(int status);
+
+/* In every array below, "k" as a column count (scores, expert_idx, mask, inv, perm, the caches,
+ * max_rows' bound T*k) stands for k + n_shared when the shape has shared experts, pair id
+ * p = i*(k + n_shared) + j, and W1/b1/W2/b2 hold E + n_shared experts; counts and offsets then
+ * have E + n_shared (+1) entries.  moe_gate writes the shared slots (expert E+s, score 1),
+ * moe_conditional_refresh sets their mask bytes to 1 and counts them in n_refresh; a mask that
+ * clears a shared slot is an error of the caller (moe_combine keeps no cache for those slots
+ * and leaves H_cache / S_cache at those positions untouched). */
 
 /* Router (Algorithm 1, "[s, idx] <- router(x)"; K activated experts per token, Conditional
  * Communication figure).  logits z = x . Wg^T (+ bg), accumulated in float; expert_idx[i][j] is

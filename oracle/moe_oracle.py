@@ -176,6 +176,34 @@ def combine(h_packed, inv, s, mask, H_cache=None, S_cache=None, use_fresh_scores
     return y
 
 
+def shared_experts(x, W1s, b1s, W2s, b2s) -> np.ndarray:
+    """Sum over the shared experts of their FFN applied to every token, float64 [T, d].
+
+    The DiT-MoE layer carries, beside the routed experts, shared experts that see every token
+    (Section 2, "Mixture-of-Experts"; Section 5.1, "Models and Datasets": two of them; supplement,
+    "More details of MoE" and its figure).  Their result is added to the routed sum without a gate
+    score, and it is computed anew in every step: it never takes part in Conditional Communication
+    (supplement, "Influence of Shared Experts").  Written out as the definition, dense:
+    out_i = sum_s ( W2s[s] gelu(W1s[s] x_i + b1s[s]) + b2s[s] ), GELU in its exact erf form.
+    """
+    from scipy.special import erf
+    x = _f64(x)
+    W1s, W2s = _f64(W1s), _f64(W2s)
+    S, F, d = W1s.shape
+    assert W2s.shape == (S, d, F) and x.shape[1] == d
+    out = np.zeros((x.shape[0], d), np.float64)
+    for e in range(S):
+        u = x @ W1s[e].T
+        if b1s is not None:
+            u = u + _f64(b1s)[e][None, :]
+        g = 0.5 * u * (1.0 + erf(u / np.sqrt(2.0)))
+        h = g @ W2s[e].T
+        if b2s is not None:
+            h = h + _f64(b2s)[e][None, :]
+        out += h
+    return out
+
+
 def num_threads() -> int:
     return int(lib().oracle_num_threads())
 
@@ -205,14 +233,25 @@ class LayerResult:
     x_packed: np.ndarray
     h_packed: np.ndarray
     y: np.ndarray
+    y_shared: Optional[np.ndarray] = None
 
 
 def moe_layer(x, Wg, bg, W1, b1, W2, b2, k: int, *, renorm_topk=False, policy=REFRESH_ALL,
               step_t=0, stride_n=1, n_units=0, H_cache=None, S_cache=None,
-              use_fresh_scores=False) -> LayerResult:
+              use_fresh_scores=False, n_shared=0) -> LayerResult:
     """One MoE layer in the order of Algorithm 1, with the Algorithm 4 decision between router
-    and dispatch.  Caches (float64) are updated in place when given."""
+    and dispatch.  Caches (float64) are updated in place when given.  With ``n_shared`` > 0 the
+    weight arrays hold E routed experts followed by n_shared shared ones; the shared experts'
+    dense result (``shared_experts``) is added to the routed y."""
     E = np.asarray(Wg).shape[0]
+    if n_shared:
+        assert np.asarray(W1).shape[0] == E + n_shared
+        W1s, W2s = np.asarray(W1)[E:], np.asarray(W2)[E:]
+        b1s = None if b1 is None else np.asarray(b1)[E:]
+        b2s = None if b2 is None else np.asarray(b2)[E:]
+        W1, W2 = np.asarray(W1)[:E], np.asarray(W2)[:E]
+        b1 = None if b1 is None else np.asarray(b1)[:E]
+        b2 = None if b2 is None else np.asarray(b2)[:E]
     z = router_logits(x, Wg, bg)
     idx = topk(z, k)
     p, s = scores(z, idx, renorm_topk)
@@ -221,4 +260,8 @@ def moe_layer(x, Wg, bg, W1, b1, W2, b2, k: int, *, renorm_topk=False, policy=RE
     xp = pack_rows(x, perm, k)
     h = expert_ffn(xp, offsets, np.arange(E, dtype=np.int32), W1, b1, W2, b2)
     y = combine(h, inv, s, mask, H_cache, S_cache, use_fresh_scores)
-    return LayerResult(z, idx, p, s, mask, R, counts, offsets, perm, inv, xp, h, y)
+    y_shared = None
+    if n_shared:
+        y_shared = shared_experts(x, W1s, b1s, W2s, b2s)
+        y = y + y_shared
+    return LayerResult(z, idx, p, s, mask, R, counts, offsets, perm, inv, xp, h, y, y_shared)

@@ -32,7 +32,7 @@ EXPORTS = ["moe_create", "moe_destroy", "moe_workspace_bytes", "moe_last_error",
 class MoeShape(ctypes.Structure):
     _fields_ = [("T_max", ctypes.c_int32), ("d", ctypes.c_int32), ("F", ctypes.c_int32),
                 ("E", ctypes.c_int32), ("k", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("renorm_topk", ctypes.c_int32)]
+                ("renorm_topk", ctypes.c_int32), ("n_shared", ctypes.c_int32)]
 
 
 class MoePolicy(ctypes.Structure):
@@ -105,20 +105,22 @@ class Policy:
     def c(self) -> MoePolicy:
         return MoePolicy(self.kind, self.step_t, self.stride_n, self.n_units, int(self.use_fresh_scores))
 
-    def refreshed_pairs(self, T: int, k: int) -> int:
+    def refreshed_pairs(self, T: int, k: int, n_shared: int = 0) -> int:
         """Number of (token, slot) pairs this policy refreshes among T tokens.  Every policy fixes it
         from its parameters alone (Algorithm 4: slot 0 always, the other slots on steps with
-        t mod n == 0), so the host knows it without reading the mask back; it sizes the FFN launch."""
+        t mod n == 0; shared-expert slots always), so the host knows it without reading the mask
+        back; it sizes the FFN launch."""
+        shared = T * n_shared
         if self.kind == REFRESH_ALL:
-            return T * k
+            return T * k + shared
         if self.kind == REFRESH_NONE:
-            return 0
+            return shared
         if self.kind == REFRESH_ALG4:
-            return T * k if self.step_t % self.stride_n == 0 else T
+            return (T * k if self.step_t % self.stride_n == 0 else T) + shared
         if self.kind == REFRESH_FRACTION_TOKEN:
-            return min(max(self.n_units, 0), T) * k
+            return min(max(self.n_units, 0), T) * k + shared
         if self.kind == REFRESH_FRACTION_PAIR:
-            return min(max(self.n_units, 0), T * k)
+            return min(max(self.n_units, 0), T * k) + shared
         raise ValueError("unknown refresh policy %r" % (self.kind,))
 
 
@@ -126,11 +128,14 @@ class Context:
     """Owns one ``moe_ctx``; methods carry the names of the C entry points."""
 
     def __init__(self, T_max: int, d: int, F: int, E: int, k: int, dtype: str = "bf16",
-                 renorm_topk: bool = False):
+                 renorm_topk: bool = False, n_shared: int = 0):
         self.T_max, self.d, self.F, self.E, self.k = T_max, d, F, E, k
+        self.n_shared = n_shared
+        self.slots = k + n_shared            # columns of every per-pair array
+        self.experts = E + n_shared          # expert ids in use (shared experts last)
         self.dtype_name = dtype
         self.torch_dtype = {"bf16": torch.bfloat16, "f32": torch.float32}[dtype]
-        shape = MoeShape(T_max, d, F, E, k, MOE_BF16 if dtype == "bf16" else MOE_F32, int(renorm_topk))
+        shape = MoeShape(T_max, d, F, E, k, MOE_BF16 if dtype == "bf16" else MOE_F32, int(renorm_topk), n_shared)
         self._h = ctypes.c_void_p()
         rc = lib().moe_create(ctypes.byref(self._h), ctypes.byref(shape))
         if rc != MOE_OK:
@@ -208,7 +213,7 @@ class LayerBuffers:
 
     def __init__(self, ctx: Context, device="cuda", with_cache: bool = False, with_debug: bool = False,
                  workspace: Optional[torch.Tensor] = None):
-        T, k, d, E = ctx.T_max, ctx.k, ctx.d, ctx.E
+        T, k, d, E = ctx.T_max, ctx.slots, ctx.d, ctx.experts
         N = T * k
         dt = ctx.torch_dtype
         dev = device
@@ -228,8 +233,8 @@ class LayerBuffers:
             ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
         self.H_cache = torch.zeros((T, k, d), dtype=dt, device=dev) if with_cache else None
         self.S_cache = torch.zeros((T, k), dtype=torch.float32, device=dev) if with_cache else None
-        self.probs = torch.empty((T, E), dtype=torch.float32, device=dev) if with_debug else None
-        self.logits = torch.empty((T, E), dtype=torch.float32, device=dev) if with_debug else None
+        self.probs = torch.empty((T, ctx.E), dtype=torch.float32, device=dev) if with_debug else None
+        self.logits = torch.empty((T, ctx.E), dtype=torch.float32, device=dev) if with_debug else None
 
 
 def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2,
@@ -242,9 +247,9 @@ def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2
     writes its index outputs only and the FFN reads the token rows through ``perm``; otherwise
     ``buf.x_packed`` is materialised first (the send buffer of the expert-parallel layout)."""
     T = x.shape[0]
-    N = T * ctx.k
+    N = T * ctx.slots
     if max_rows is None and policy is not None:
-        max_rows = policy.refreshed_pairs(T, ctx.k)
+        max_rows = policy.refreshed_pairs(T, ctx.k, ctx.n_shared)
     ctx.moe_gate(x, Wg, bg, buf.scores[:T], buf.expert_idx[:T], buf.probs, buf.logits)
     mask = None
     if policy is not None:

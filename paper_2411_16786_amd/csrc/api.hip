@@ -31,6 +31,9 @@ int hip_result(moe_ctx* ctx, hipError_t err, const char* what)
 }
 
 bool is_bf16(const moe_ctx* ctx) { return ctx->shape.dtype == MOE_BF16; }
+// slots per token and expert ids in use, shared experts included
+int slots(const moe_ctx* ctx) { return ctx->shape.k + ctx->shape.n_shared; }
+int experts(const moe_ctx* ctx) { return ctx->shape.E + ctx->shape.n_shared; }
 size_t elem_bytes(const moe_ctx* ctx) { return is_bf16(ctx) ? 2 : 4; }
 
 int check_T(moe_ctx* ctx, int32_t T)
@@ -49,10 +52,10 @@ int moe_create(moe_ctx** out, const moe_shape* s)
     *out = nullptr;
     if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_DTYPE;
     if (s->T_max < 0 || s->d < 1 || s->F < 1 || s->E < 1 || s->k < 1) return MOE_ERR_SHAPE;
-    if (s->k > s->E || s->E > 64) return MOE_ERR_SHAPE;
+    if (s->n_shared < 0 || s->k > s->E || s->E + s->n_shared > 64) return MOE_ERR_SHAPE;
     const int mult = (s->dtype == MOE_BF16) ? 64 : 16;
     if (s->d % mult != 0 || s->F % mult != 0) return MOE_ERR_SHAPE;
-    const long long rows = static_cast<long long>(s->T_max) * s->k;
+    const long long rows = static_cast<long long>(s->T_max) * (s->k + s->n_shared);
     const long long widest = s->d > s->F ? s->d : s->F;
     if (rows * widest >= (1ll << 31)) return MOE_ERR_SHAPE;
     if (static_cast<long long>(s->T_max) * s->E >= (1ll << 31)) return MOE_ERR_SHAPE;
@@ -75,7 +78,7 @@ int moe_destroy(moe_ctx* ctx)
 size_t moe_workspace_bytes(const moe_ctx* ctx)
 {
     if (!ctx) return 0;
-    const size_t rows = static_cast<size_t>(ctx->shape.T_max) * ctx->shape.k;
+    const size_t rows = static_cast<size_t>(ctx->shape.T_max) * slots(ctx);
     const size_t hidden = rows * ctx->shape.F * (ctx->shape.dtype == MOE_BF16 ? 2 : 4);
     return ((hidden + 255) / 256) * 256 + 4096;
 }
@@ -106,8 +109,8 @@ int moe_gate(moe_ctx* ctx, const void* x, const void* Wg, const float* bg, int32
     if (T == 0) return MOE_OK;
     const moe_shape& s = ctx->shape;
     return hip_result(ctx,
-                      launch_gate(is_bf16(ctx), x, Wg, bg, T, s.d, s.E, s.k, s.renorm_topk, scores, expert_idx,
-                                  probs_all, logits, static_cast<hipStream_t>(stream)),
+                      launch_gate(is_bf16(ctx), x, Wg, bg, T, s.d, s.E, s.k, s.n_shared, s.renorm_topk, scores,
+                                  expert_idx, probs_all, logits, static_cast<hipStream_t>(stream)),
                       "moe_gate");
 }
 
@@ -126,14 +129,14 @@ int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* ex
     switch (policy->kind) {
     case MOE_REFRESH_ALL:
     case MOE_REFRESH_NONE:
-        return hip_result(ctx, launch_refresh_simple(policy->kind, T, s.k, 0, 1, mask, n_refresh, st),
+        return hip_result(ctx, launch_refresh_simple(policy->kind, T, s.k, s.n_shared, 0, 1, mask, n_refresh, st),
                           "moe_conditional_refresh");
     case MOE_REFRESH_ALG4:
         if (policy->stride_n < 1 || policy->step_t < 0)
             return fail(ctx, MOE_ERR_POLICY, "ALG4 needs step_t >= 0 and stride_n >= 1 (got %ld, %ld)",
                         policy->step_t, policy->stride_n);
         return hip_result(ctx,
-                          launch_refresh_simple(MOE_REFRESH_ALG4, T, s.k, policy->step_t, policy->stride_n, mask,
+                          launch_refresh_simple(MOE_REFRESH_ALG4, T, s.k, s.n_shared, policy->step_t, policy->stride_n, mask,
                                                 n_refresh, st),
                           "moe_conditional_refresh");
     case MOE_REFRESH_FRACTION_TOKEN:
@@ -141,7 +144,7 @@ int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* ex
             return fail(ctx, MOE_ERR_POLICY, "FRACTION_TOKEN n_units=%ld outside 0..T=%ld", policy->n_units, T);
         if (!scores) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: scores is null");
         return hip_result(ctx,
-                          launch_refresh_select(scores, T, s.k, 0, policy->n_units, true, policy->n_units * s.k,
+                          launch_refresh_select(scores, T, s.k, s.n_shared, 0, policy->n_units, true, policy->n_units * s.k,
                                                 mask, n_refresh, st),
                           "moe_conditional_refresh");
     case MOE_REFRESH_FRACTION_PAIR: {
@@ -149,13 +152,13 @@ int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* ex
             return fail(ctx, MOE_ERR_POLICY, "FRACTION_PAIR n_units=%ld outside 0..T*k=%ld", policy->n_units, N);
         if (!scores) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: scores is null");
         if (policy->n_units == N)
-            return hip_result(ctx, launch_refresh_simple(MOE_REFRESH_ALL, T, s.k, 0, 1, mask, n_refresh, st),
+            return hip_result(ctx, launch_refresh_simple(MOE_REFRESH_ALL, T, s.k, s.n_shared, 0, 1, mask, n_refresh, st),
                               "moe_conditional_refresh");
         // slots before `slot` are refreshed for every token, slot `slot` for its m best tokens
         const int slot = T > 0 ? policy->n_units / T : 0;
         const int m = T > 0 ? policy->n_units % T : 0;
         return hip_result(ctx,
-                          launch_refresh_select(scores, T, s.k, slot, m, false, policy->n_units, mask, n_refresh, st),
+                          launch_refresh_select(scores, T, s.k, s.n_shared, slot, m, false, policy->n_units, mask, n_refresh, st),
                           "moe_conditional_refresh");
     }
     default:
@@ -174,7 +177,7 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const u
         return fail(ctx, MOE_ERR_NULL, "moe_dispatch: null pointer");
     const moe_shape& s = ctx->shape;
     return hip_result(ctx,
-                      launch_dispatch(is_bf16(ctx), x, expert_idx, mask, T, s.d, s.E, s.k, x_packed, counts, offsets,
+                      launch_dispatch(is_bf16(ctx), x, expert_idx, mask, T, s.d, experts(ctx), slots(ctx), x_packed, counts, offsets,
                                       perm, inv, static_cast<hipStream_t>(stream)),
                       "moe_dispatch");
 }
@@ -189,8 +192,8 @@ static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, 
     const moe_shape& s = ctx->shape;
     if (n_segments < 1 || n_segments > 1024)
         return fail(ctx, MOE_ERR_SHAPE, "n_segments=%ld outside 1..1024", n_segments);
-    if (max_rows < 0 || static_cast<long long>(max_rows) > static_cast<long long>(s.T_max) * s.k)
-        return fail(ctx, MOE_ERR_SHAPE, "max_rows=%ld outside 0..T_max*k=%ld", max_rows, static_cast<long>(s.T_max) * s.k);
+    if (max_rows < 0 || static_cast<long long>(max_rows) > static_cast<long long>(s.T_max) * slots(ctx))
+        return fail(ctx, MOE_ERR_SHAPE, "max_rows=%ld outside 0..T_max*slots=%ld", max_rows, static_cast<long>(s.T_max) * slots(ctx));
     if (!x_rows || !seg_offsets || !seg_expert || !W1 || !W2 || !h_packed) {
         std::snprintf(ctx->err, sizeof(ctx->err), "%s: null pointer", who);
         return MOE_ERR_NULL;
@@ -200,7 +203,7 @@ static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, 
         return MOE_ERR_WORKSPACE;
     }
     return hip_result(ctx,
-                      launch_expert_ffn(is_bf16(ctx), x_rows, row_pairs, s.k, seg_offsets, seg_expert, n_segments,
+                      launch_expert_ffn(is_bf16(ctx), x_rows, row_pairs, slots(ctx), seg_offsets, seg_expert, n_segments,
                                         max_rows, s.d, s.F, W1, b1, W2, b2, h_packed, workspace,
                                         static_cast<hipStream_t>(stream)),
                       who);
@@ -240,7 +243,8 @@ int moe_combine(moe_ctx* ctx, const void* h_packed, const int32_t* inv, const fl
         return fail(ctx, MOE_ERR_NULL, "moe_combine: H_cache and S_cache must be given together");
     const moe_shape& s = ctx->shape;
     return hip_result(ctx,
-                      launch_combine(is_bf16(ctx), h_packed, inv, scores, mask, T, s.d, s.k, H_cache, S_cache,
+                      launch_combine(is_bf16(ctx), h_packed, inv, scores, mask, T, s.d, slots(ctx), s.k, H_cache,
+                                     S_cache,
                                      use_fresh_scores ? 1 : 0, y, static_cast<hipStream_t>(stream)),
                       "moe_combine");
 }

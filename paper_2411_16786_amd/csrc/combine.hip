@@ -14,11 +14,13 @@ namespace dicemoe {
 
 // KK > 0: k == KK, the per-pair scalars (packed row, score, fresh or reused) are read once per token
 // and the k row loads of a 16-byte column slice are issued together; KK == 0: any k, pair by pair.
+// Slots k_cached..k-1 (shared experts, fresh in every step) are never written to the caches.
 template <typename T, int KK>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_packed, const int32_t* __restrict__ inv,
                                                       const float* __restrict__ scores,
                                                       const uint8_t* __restrict__ mask, int T_tok, int d, int k,
-                                                      T* H_cache, float* S_cache, int use_fresh, T* __restrict__ y)
+                                                      int k_cached, T* H_cache, float* S_cache, int use_fresh,
+                                                      T* __restrict__ y)
 {
     constexpr int V = Store<T>::kVec;
     const int tok = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -61,7 +63,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
                 Store<T>::unpack(v[j], f);
 #pragma unroll
                 for (int t = 0; t < V; ++t) acc[t] = fmaf(sc[j], f[t], acc[t]);
-                if (fresh[j] && hc) hc[(p0 + j) * nvec + c] = v[j];
+                if (fresh[j] && hc && j < k_cached) hc[(p0 + j) * nvec + c] = v[j];
             }
             const uint4 packed = Store<T>::pack(acc);
             yo[c] = u32x4_t{packed.x, packed.y, packed.z, packed.w};
@@ -80,7 +82,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
                     const int r = inv[p];
                     if (r >= 0) v = hp[static_cast<size_t>(r) * nvec + c];
                     s = scores[p];
-                    if (hc) hc[p * nvec + c] = v;
+                    if (hc && j < k_cached) hc[p * nvec + c] = v;
                 } else {
                     v = hc[p * nvec + c];
                     s = use_fresh ? scores[p] : S_cache[p];
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
             yo[c] = u32x4_t{packed.x, packed.y, packed.z, packed.w};
         }
     }
-    if (S_cache && lane < k) {
+    if (S_cache && lane < k_cached) {
         const size_t p = p0 + lane;
         if (mask == nullptr || mask[p] != 0) S_cache[p] = scores[p];
     }
@@ -102,13 +104,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
 
 template <typename T>
 static void launch_combine_t(const void* h_packed, const int32_t* inv, const float* scores, const uint8_t* mask,
-                             int T_tok, int d, int k, void* H_cache, float* S_cache, int use_fresh, void* y,
-                             hipStream_t stream)
+                             int T_tok, int d, int k, int k_cached, void* H_cache, float* S_cache, int use_fresh,
+                             void* y, hipStream_t stream)
 {
     const int blocks = (T_tok + 3) / 4;
 #define DICEMOE_COMBINE(KK_)                                                                                     \
     hipLaunchKernelGGL((combine_kernel<T, KK_>), dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(h_packed), \
-                       inv, scores, mask, T_tok, d, k, static_cast<T*>(H_cache), S_cache, use_fresh, static_cast<T*>(y))
+                       inv, scores, mask, T_tok, d, k, k_cached, static_cast<T*>(H_cache), S_cache, use_fresh,            \
+                       static_cast<T*>(y))
     if (k == 1) DICEMOE_COMBINE(1);
     else if (k == 2) DICEMOE_COMBINE(2);
     else if (k == 3) DICEMOE_COMBINE(3);
@@ -118,12 +121,12 @@ static void launch_combine_t(const void* h_packed, const int32_t* inv, const flo
 }
 
 hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, const float* scores,
-                          const uint8_t* mask, int T_tok, int d, int k, void* H_cache, float* S_cache,
-                          int use_fresh, void* y, hipStream_t stream)
+                          const uint8_t* mask, int T_tok, int d, int k, int k_cached, void* H_cache,
+                          float* S_cache, int use_fresh, void* y, hipStream_t stream)
 {
     if (T_tok == 0) return hipSuccess;
-    if (bf16) launch_combine_t<bf16_t>(h_packed, inv, scores, mask, T_tok, d, k, H_cache, S_cache, use_fresh, y, stream);
-    else launch_combine_t<float>(h_packed, inv, scores, mask, T_tok, d, k, H_cache, S_cache, use_fresh, y, stream);
+    if (bf16) launch_combine_t<bf16_t>(h_packed, inv, scores, mask, T_tok, d, k, k_cached, H_cache, S_cache, use_fresh, y, stream);
+    else launch_combine_t<float>(h_packed, inv, scores, mask, T_tok, d, k, k_cached, H_cache, S_cache, use_fresh, y, stream);
     return hipGetLastError();
 }
 

@@ -17,7 +17,7 @@ namespace dicemoe {
 template <typename T, int EMAX, int NCH, int TPW, bool LDS_W>
 __global__ __launch_bounds__(256) void gate_kernel(const T* __restrict__ x, const T* __restrict__ Wg,
                                                    const float* __restrict__ bg, int T_tok, int d, int E,
-                                                   int k, int renorm, float* __restrict__ scores,
+                                                   int k, int n_shared, int renorm, float* __restrict__ scores,
                                                    int32_t* __restrict__ expert_idx,
                                                    float* __restrict__ probs_all, float* __restrict__ logits)
 {
@@ -111,9 +111,14 @@ __global__ __launch_bounds__(256) void gate_kernel(const T* __restrict__ x, cons
             s_me = p_me / ssum;
         }
         if (tok < T_tok) {
+            const size_t row = static_cast<size_t>(tok) * (k + n_shared);
             if (chosen) {
-                scores[static_cast<size_t>(tok) * k + rank] = s_me;
-                expert_idx[static_cast<size_t>(tok) * k + rank] = lane;
+                scores[row + rank] = s_me;
+                expert_idx[row + rank] = lane;
+            }
+            if (lane < n_shared) {                      // shared experts: every token, score 1
+                scores[row + k + lane] = 1.0f;
+                expert_idx[row + k + lane] = E + lane;
             }
             if (is_expert) {
                 if (probs_all) probs_all[static_cast<size_t>(tok) * E + lane] = p_me;
@@ -136,7 +141,7 @@ __global__ __launch_bounds__(256) void gate_kernel(const T* __restrict__ x, cons
 template <int NB, int U>
 __global__ __launch_bounds__(256) void gate_mfma_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wg,
                                                         const float* __restrict__ bg, int T_tok, int d, int E,
-                                                        int k, int renorm, float* __restrict__ scores,
+                                                        int k, int n_shared, int renorm, float* __restrict__ scores,
                                                         int32_t* __restrict__ expert_idx,
                                                         float* __restrict__ probs_all, float* __restrict__ logits)
 {
@@ -220,9 +225,14 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const bf16_t* __restrict
             const float ssum = wave_sum(chosen ? p_me : 0.f);
             s_me = p_me / ssum;
         }
+        const size_t row = static_cast<size_t>(tk) * (k + n_shared);
         if (chosen) {
-            scores[static_cast<size_t>(tk) * k + rank] = s_me;
-            expert_idx[static_cast<size_t>(tk) * k + rank] = lane;
+            scores[row + rank] = s_me;
+            expert_idx[row + rank] = lane;
+        }
+        if (lane < n_shared) {                          // shared experts: every token, score 1
+            scores[row + k + lane] = 1.0f;
+            expert_idx[row + k + lane] = E + lane;
         }
         if (is_expert) {
             if (probs_all) probs_all[static_cast<size_t>(tk) * E + lane] = p_me;
@@ -233,7 +243,7 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const bf16_t* __restrict
 
 template <int NB>
 static hipError_t launch_gate_mfma_nb(const bf16_t* xb, const bf16_t* wb, const float* bg, int T_tok, int d, int E, int k,
-                                      int renorm, float* scores, int32_t* idx, float* probs, float* logits,
+                                      int n_shared, int renorm, float* scores, int32_t* idx, float* probs, float* logits,
                                       hipStream_t stream)
 {
     const int blocks = (T_tok + 15) / 16;
@@ -243,7 +253,7 @@ static hipError_t launch_gate_mfma_nb(const bf16_t* xb, const bf16_t* wb, const 
 #define DICEMOE_GATE_U(U_)                                                                                          \
     if (need <= U_ || U_ == UMAX) {                                                                                 \
         hipLaunchKernelGGL((gate_mfma_kernel<NB, U_>), dim3(blocks), dim3(256), 0, stream, xb, wb, bg, T_tok, d, E, \
-                           k, renorm, scores, idx, probs, logits);                                                  \
+                           k, n_shared, renorm, scores, idx, probs, logits);                                                  \
         return hipGetLastError();                                                                                   \
     }
     DICEMOE_GATE_U(3)
@@ -257,19 +267,19 @@ static hipError_t launch_gate_mfma_nb(const bf16_t* xb, const bf16_t* wb, const 
 }
 
 static hipError_t launch_gate_mfma(const void* x, const void* Wg, const float* bg, int T_tok, int d, int E, int k,
-                                   int renorm, float* scores, int32_t* idx, float* probs, float* logits,
+                                   int n_shared, int renorm, float* scores, int32_t* idx, float* probs, float* logits,
                                    hipStream_t stream)
 {
     const bf16_t* xb = static_cast<const bf16_t*>(x);
     const bf16_t* wb = static_cast<const bf16_t*>(Wg);
-    if (E <= 16) return launch_gate_mfma_nb<1>(xb, wb, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream);
-    if (E <= 32) return launch_gate_mfma_nb<2>(xb, wb, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream);
-    return launch_gate_mfma_nb<4>(xb, wb, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream);
+    if (E <= 16) return launch_gate_mfma_nb<1>(xb, wb, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream);
+    if (E <= 32) return launch_gate_mfma_nb<2>(xb, wb, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream);
+    return launch_gate_mfma_nb<4>(xb, wb, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream);
 }
 
 template <typename T, int EMAX, int NCH, int TPW>
 static hipError_t launch_gate_cfg(const void* x, const void* Wg, const float* bg, int T_tok, int d, int E, int k,
-                                  int renorm, float* scores, int32_t* idx, float* probs, float* logits,
+                                  int n_shared, int renorm, float* scores, int32_t* idx, float* probs, float* logits,
                                   hipStream_t stream)
 {
     const int tokens_per_block = 4 * TPW;
@@ -277,11 +287,11 @@ static hipError_t launch_gate_cfg(const void* x, const void* Wg, const float* bg
     const size_t w_bytes = static_cast<size_t>(E) * d * sizeof(T);
     if (w_bytes <= 64 * 1024) {
         hipLaunchKernelGGL((gate_kernel<T, EMAX, NCH, TPW, true>), dim3(blocks), dim3(256), w_bytes, stream,
-                           static_cast<const T*>(x), static_cast<const T*>(Wg), bg, T_tok, d, E, k, renorm,
+                           static_cast<const T*>(x), static_cast<const T*>(Wg), bg, T_tok, d, E, k, n_shared, renorm,
                            scores, idx, probs, logits);
     } else {
         hipLaunchKernelGGL((gate_kernel<T, EMAX, NCH, TPW, false>), dim3(blocks), dim3(256), 0, stream,
-                           static_cast<const T*>(x), static_cast<const T*>(Wg), bg, T_tok, d, E, k, renorm,
+                           static_cast<const T*>(x), static_cast<const T*>(Wg), bg, T_tok, d, E, k, n_shared, renorm,
                            scores, idx, probs, logits);
     }
     return hipGetLastError();
@@ -290,13 +300,13 @@ static hipError_t launch_gate_cfg(const void* x, const void* Wg, const float* bg
 // NCH = 16-byte slices per lane and row (ceil(d / V / 64)); TPW shrinks as the per-lane state grows
 template <typename T, int EMAX, int TPW>
 static hipError_t launch_gate_e(const void* x, const void* Wg, const float* bg, int T_tok, int d, int E, int k,
-                                int renorm, float* scores, int32_t* idx, float* probs, float* logits,
+                                int n_shared, int renorm, float* scores, int32_t* idx, float* probs, float* logits,
                                 hipStream_t stream, bool* ok)
 {
     const int nch = (d / Store<T>::kVec + kWave - 1) / kWave;
     *ok = true;
 #define DICEMOE_GATE_CASE(N_, TPW_) \
-    return launch_gate_cfg<T, EMAX, N_, TPW_>(x, Wg, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream)
+    return launch_gate_cfg<T, EMAX, N_, TPW_>(x, Wg, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream)
     if (nch <= 1) DICEMOE_GATE_CASE(1, TPW);
     if (nch <= 2) DICEMOE_GATE_CASE(2, TPW);
     if (nch <= 3) DICEMOE_GATE_CASE(3, TPW);
@@ -310,21 +320,21 @@ static hipError_t launch_gate_e(const void* x, const void* Wg, const float* bg, 
 
 template <typename T>
 static hipError_t launch_gate_t(const void* x, const void* Wg, const float* bg, int T_tok, int d, int E, int k,
-                                int renorm, float* scores, int32_t* idx, float* probs, float* logits,
+                                int n_shared, int renorm, float* scores, int32_t* idx, float* probs, float* logits,
                                 hipStream_t stream, bool* ok)
 {
-    if (E <= 8) return launch_gate_e<T, 8, 4>(x, Wg, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream, ok);
-    if (E <= 16) return launch_gate_e<T, 16, 2>(x, Wg, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream, ok);
-    if (E <= 32) return launch_gate_e<T, 32, 1>(x, Wg, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream, ok);
-    return launch_gate_e<T, 64, 1>(x, Wg, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream, ok);
+    if (E <= 8) return launch_gate_e<T, 8, 4>(x, Wg, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream, ok);
+    if (E <= 16) return launch_gate_e<T, 16, 2>(x, Wg, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream, ok);
+    if (E <= 32) return launch_gate_e<T, 32, 1>(x, Wg, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream, ok);
+    return launch_gate_e<T, 64, 1>(x, Wg, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream, ok);
 }
 
 hipError_t launch_gate(bool bf16, const void* x, const void* Wg, const float* bg, int T_tok, int d, int E, int k,
-                       int renorm, float* scores, int32_t* idx, float* probs, float* logits, hipStream_t stream)
+                       int n_shared, int renorm, float* scores, int32_t* idx, float* probs, float* logits, hipStream_t stream)
 {
-    if (bf16) return launch_gate_mfma(x, Wg, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream);
+    if (bf16) return launch_gate_mfma(x, Wg, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream);
     bool ok = true;
-    hipError_t err = launch_gate_t<float>(x, Wg, bg, T_tok, d, E, k, renorm, scores, idx, probs, logits, stream, &ok);
+    hipError_t err = launch_gate_t<float>(x, Wg, bg, T_tok, d, E, k, n_shared, renorm, scores, idx, probs, logits, stream, &ok);
     if (!ok) return hipErrorInvalidValue;     // float rows beyond 16 slices per lane (4096 columns)
     return err;
 }

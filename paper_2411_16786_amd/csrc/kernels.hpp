@@ -6,25 +6,30 @@
 
 namespace dicemoe {
 
+// scores / idx have k + n_shared columns: the k routed slots, then slot k+s = (expert E+s, score 1)
 hipError_t launch_gate(bool bf16, const void* x, const void* Wg, const float* bg, int T_tok, int d, int E, int k,
-                       int renorm, float* scores, int32_t* idx, float* probs, float* logits, hipStream_t stream);
+                       int n_shared, int renorm, float* scores, int32_t* idx, float* probs, float* logits,
+                       hipStream_t stream);
 
-// kind: 0 all, 1 Algorithm 4, 4 none (elementwise policies)
-hipError_t launch_refresh_simple(int kind, int T_tok, int k, int step_t, int stride_n, uint8_t* mask,
+// kind: 0 all, 1 Algorithm 4, 4 none (elementwise policies).  mask has k + n_shared columns; the
+// shared slots are refreshed under every policy
+hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int step_t, int stride_n, uint8_t* mask,
                                  int32_t* n_refresh, hipStream_t stream);
 // exact top-m selection of tokens by scores[i*k + slot] (descending, ties to the lower token);
 // token_mode: selected tokens get all k slots; otherwise slots < slot are all refreshed, slot
 // `slot` follows the selection and later slots are not refreshed
-hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int slot, int m, bool token_mode,
-                                 int n_refresh_value, uint8_t* mask, int32_t* n_refresh, hipStream_t stream);
+// (n_refresh_value counts routed pairs; the shared slots are added here)
+hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int n_shared, int slot, int m,
+                                 bool token_mode, int n_refresh_value, uint8_t* mask, int32_t* n_refresh,
+                                 hipStream_t stream);
 
 hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const uint8_t* mask, int T_tok, int d,
                            int E, int k, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
                            int32_t* inv, hipStream_t stream);
 
 hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, const float* scores,
-                          const uint8_t* mask, int T_tok, int d, int k, void* H_cache, float* S_cache,
-                          int use_fresh, void* y, hipStream_t stream);
+                          const uint8_t* mask, int T_tok, int d, int k, int k_cached, void* H_cache,
+                          float* S_cache, int use_fresh, void* y, hipStream_t stream);
 
 // x_rows is the packed buffer (row_index == nullptr) or the token matrix with row_index[r] / row_div
 // naming the row that packed row r reads

@@ -11,17 +11,20 @@
 
 namespace dicemoe {
 
-__global__ __launch_bounds__(256) void refresh_simple_kernel(int kind, int N, int k, int off_step,
+// kc = columns of the mask (k routed slots, then the shared-expert slots, which are always refreshed)
+__global__ __launch_bounds__(256) void refresh_simple_kernel(int kind, int N, int kc, int k, int off_step,
                                                              uint8_t* __restrict__ mask,
                                                              int32_t* __restrict__ n_refresh, int n_value)
 {
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p == 0) *n_refresh = n_value;
     if (p >= N) return;
+    const int j = p % kc;
     uint8_t m;
-    if (kind == 0) m = 1;                                   // every pair
+    if (j >= k) m = 1;                                      // shared expert: fresh in every step
+    else if (kind == 0) m = 1;                              // every pair
     else if (kind == 4) m = 0;                              // no pair
-    else m = ((p % k) == 0 || !off_step) ? 1 : 0;           // top-1 slot always, others on t mod n == 0
+    else m = (j == 0 || !off_step) ? 1 : 0;                 // top-1 slot always, others on t mod n == 0
     mask[p] = m;
 }
 
@@ -35,7 +38,7 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 
 __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float* __restrict__ scores, int T_tok,
-                                                                    int k, int slot, int m, int token_mode,
+                                                                    int kc, int k, int slot, int m, int token_mode,
                                                                     int n_value, uint8_t* __restrict__ mask,
                                                                     int32_t* __restrict__ n_refresh)
 {
@@ -55,7 +58,7 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
             const uint32_t prefix = s_prefix;       // both stable until the end of this pass
             const uint32_t rem = s_remaining;
             for (int i = tid; i < T_tok; i += kSelThreads) {
-                const uint32_t key = order_key(scores[static_cast<size_t>(i) * k + slot]);
+                const uint32_t key = order_key(scores[static_cast<size_t>(i) * kc + slot]);
                 const bool in_play = (pass == 0) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
                 if (in_play) atomicAdd(&hist[(key >> shift) & 255u], 1u);
             }
@@ -95,7 +98,7 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
         if (!need_select) {
             sel = (m > 0);
         } else {
-            const uint32_t key = valid ? order_key(scores[static_cast<size_t>(i) * k + slot]) : 0u;
+            const uint32_t key = valid ? order_key(scores[static_cast<size_t>(i) * kc + slot]) : 0u;
             const bool eq = valid && key == thr;
             const uint64_t b = __ballot(eq);
             if (lane_id() == 0) wave_cnt[wave] = __popcll(b);
@@ -112,35 +115,39 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
             __syncthreads();
         }
         if (valid) {
-            for (int j = 0; j < k; ++j) {
+            for (int j = 0; j < kc; ++j) {
                 uint8_t v;
-                if (token_mode) v = sel ? 1 : 0;
+                if (j >= k) v = 1;                                   // shared expert: fresh in every step
+                else if (token_mode) v = sel ? 1 : 0;
                 else v = (j < slot) ? 1 : (j == slot ? (sel ? 1 : 0) : 0);
-                mask[static_cast<size_t>(i) * k + j] = v;
+                mask[static_cast<size_t>(i) * kc + j] = v;
             }
         }
     }
 }
 
-hipError_t launch_refresh_simple(int kind, int T_tok, int k, int step_t, int stride_n, uint8_t* mask,
+hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int step_t, int stride_n, uint8_t* mask,
                                  int32_t* n_refresh, hipStream_t stream)
 {
-    const int N = T_tok * k;
+    const int kc = k + n_shared;
+    const int N = T_tok * kc;
     int off_step = 0, n_value = 0;
-    if (kind == 0) n_value = N;
+    if (kind == 0) n_value = T_tok * k;
     else if (kind == 4) n_value = 0;
-    else { off_step = (step_t % stride_n) != 0; n_value = off_step ? T_tok : N; }
+    else { off_step = (step_t % stride_n) != 0; n_value = off_step ? T_tok : T_tok * k; }
+    n_value += T_tok * n_shared;
     const int blocks = N > 0 ? (N + 255) / 256 : 1;
-    hipLaunchKernelGGL(refresh_simple_kernel, dim3(blocks), dim3(256), 0, stream, kind, N, k, off_step, mask,
+    hipLaunchKernelGGL(refresh_simple_kernel, dim3(blocks), dim3(256), 0, stream, kind, N, kc, k, off_step, mask,
                        n_refresh, n_value);
     return hipGetLastError();
 }
 
-hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int slot, int m, bool token_mode,
-                                 int n_refresh_value, uint8_t* mask, int32_t* n_refresh, hipStream_t stream)
+hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int n_shared, int slot, int m,
+                                 bool token_mode, int n_refresh_value, uint8_t* mask, int32_t* n_refresh,
+                                 hipStream_t stream)
 {
-    hipLaunchKernelGGL(refresh_select_kernel, dim3(1), dim3(kSelThreads), 0, stream, scores, T_tok, k, slot, m,
-                       token_mode ? 1 : 0, n_refresh_value, mask, n_refresh);
+    hipLaunchKernelGGL(refresh_select_kernel, dim3(1), dim3(kSelThreads), 0, stream, scores, T_tok, k + n_shared, k,
+                       slot, m, token_mode ? 1 : 0, n_refresh_value + T_tok * n_shared, mask, n_refresh);
     return hipGetLastError();
 }
 

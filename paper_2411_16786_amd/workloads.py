@@ -114,11 +114,15 @@ def make_weights(c: MoEConfig, rng: np.random.Generator, E: Optional[int] = None
 
 
 def make_layer(cfg: int, layer: int = 0, bump: int = 0, with_experts: bool = True,
-               T: Optional[int] = None) -> LayerInputs:
+               T: Optional[int] = None, n_shared: int = 0) -> LayerInputs:
     """Inputs of one MoE layer of workload ``cfg``.
 
     ``T`` may shrink the token count (same distributions) for tests that need a
     small case of a big workload's shape.  Draw order is fixed: x, Wg, bg, W1, W2.
+    With ``n_shared`` > 0 the weights of that many shared experts (same shape and
+    distribution as the routed ones, drawn from a generator of their own so that the
+    routed values do not move) follow the routed experts in W1 and W2; the DiT-MoE
+    models of Section 5.1 carry two.
     """
     c = CONFIGS[cfg]
     T = c.T if T is None else T
@@ -141,6 +145,11 @@ def make_layer(cfg: int, layer: int = 0, bump: int = 0, with_experts: bool = Tru
         rng.standard_normal(1, dtype=np.float32)  # keep the stream position independent of bg
     if with_experts:
         W1, W2 = make_weights(c, rng)
+        if n_shared > 0:
+            rng_s = np.random.Generator(np.random.PCG64([seed, 0x5AED]))
+            W1s, W2s = make_weights(c, rng_s, E=n_shared)
+            W1 = np.concatenate([W1, W1s], axis=0)
+            W2 = np.concatenate([W2, W2s], axis=0)
     else:
         W1 = W2 = None
     return LayerInputs(c, seed, x, Wg, bg, W1, W2)

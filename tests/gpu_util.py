@@ -72,7 +72,7 @@ def topk_margin(z: np.ndarray, k: int) -> float:
     return float(np.min(zs[:, :kk - 1] - zs[:, 1:kk]))
 
 
-def pick_layer(cfg: int, layer: int = 0, T=None, with_experts=True, margin=1e-4, k=None):
+def pick_layer(cfg: int, layer: int = 0, T=None, with_experts=True, margin=1e-4, k=None, n_shared=0):
     """Seeded inputs of a workload whose routing is free of near-ties (so that float and double
     logits must agree on the top-K); the seed is bumped until that holds."""
     for bump in range(20):
@@ -80,12 +80,13 @@ def pick_layer(cfg: int, layer: int = 0, T=None, with_experts=True, margin=1e-4,
         z = O.router_logits(li.x, li.Wg, li.bg)
         if topk_margin(z, li.cfg.k if k is None else k) >= margin:
             if with_experts:
-                li = WL.make_layer(cfg, layer=layer, bump=bump, with_experts=True, T=T)
+                li = WL.make_layer(cfg, layer=layer, bump=bump, with_experts=True, T=T, n_shared=n_shared)
             return li, z
     raise AssertionError("no seed without near-ties found")
 
 
-def assert_close_storage(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", end_to_end=True):
+def assert_close_storage(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "", end_to_end=True,
+                         wide_range=False):
     got = got.astype(np.float64)
     ref = ref.astype(np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
@@ -98,7 +99,11 @@ def assert_close_storage(got: np.ndarray, ref: np.ndarray, dtype: str, what: str
         assert err.max() <= 1e-5 * scale, f"{what}: max-abs {err.max():.3e} vs scale {scale:.3e}"
         assert rel_l2 <= 1e-5, f"{what}: rel-L2 {rel_l2:.3e}"
     elif end_to_end:
-        assert err.max() <= 2e-2, f"{what}: max-abs {err.max():.3e}"
+        # the absolute bound is fit to outputs of magnitude up to about 2 (the routed layer, scores
+        # below 1); ungated shared experts push |y| past 4, where one bf16 rounding of the output
+        # alone costs up to 1.6e-2, so there (wide_range) the bound grows with the largest magnitude
+        abs_tol = 2e-2 * max(1.0, scale / 2.0) if wide_range else 2e-2
+        assert err.max() <= abs_tol, f"{what}: max-abs {err.max():.3e} (bound {abs_tol:.3e})"
         assert rel_l2 <= 1e-2, f"{what}: rel-L2 {rel_l2:.3e}"
     else:
         # one bf16 rounding of the result: half an ulp = 2^-9 relative, plus float accumulation noise
@@ -110,12 +115,14 @@ def assert_close_storage(got: np.ndarray, ref: np.ndarray, dtype: str, what: str
 class GpuLayer:
     """Uploads one layer's inputs and runs the HIP path stage by stage."""
 
-    def __init__(self, x, Wg, bg, W1, b1, W2, b2, k, dtype, T_max=None, renorm=False, with_cache=False):
+    def __init__(self, x, Wg, bg, W1, b1, W2, b2, k, dtype, T_max=None, renorm=False, with_cache=False,
+                 n_shared=0):
         self.dtype = dtype
         T, d = x.shape
         E = Wg.shape[0]
         F = W1.shape[1] if W1 is not None else d * 4
-        self.ctx = B.Context(T_max or T, d, F, E, k, dtype, renorm_topk=renorm)
+        assert W1 is None or W1.shape[0] == E + n_shared     # shared experts' weights follow the routed ones
+        self.ctx = B.Context(T_max or T, d, F, E, k, dtype, renorm_topk=renorm, n_shared=n_shared)
         self.x = to_dev(x, dtype)
         self.Wg = to_dev(Wg, dtype)
         self.bg = f32_dev(bg)

@@ -46,12 +46,15 @@ def test_struct_layouts_match_the_header():
     (dict(T_max=64, d=60, F=256, E=4, k=2, dtype="f32"), B.MOE_ERR_SHAPE),       # d % 16
     (dict(T_max=64, d=96, F=256, E=4, k=2, dtype="bf16"), B.MOE_ERR_SHAPE),      # d % 64 for bf16
     (dict(T_max=-1, d=64, F=256, E=4, k=2, dtype="f32"), B.MOE_ERR_SHAPE),
+    (dict(T_max=64, d=64, F=256, E=4, k=2, dtype="f32", n_shared=2), 0),
+    (dict(T_max=64, d=64, F=256, E=4, k=2, dtype="f32", n_shared=-1), B.MOE_ERR_SHAPE),
+    (dict(T_max=64, d=64, F=256, E=63, k=2, dtype="f32", n_shared=2), B.MOE_ERR_SHAPE),  # E + shared > 64
     (dict(T_max=1 << 22, d=2048, F=8192, E=16, k=2, dtype="bf16"), B.MOE_ERR_SHAPE),  # index overflow
 ])
 def test_create_validates_shape(kw, status):
     if status == 0:
         ctx = B.Context(**kw)
-        assert ctx.workspace_bytes() >= kw["T_max"] * kw["k"] * kw["F"] * 4
+        assert ctx.workspace_bytes() >= kw["T_max"] * (kw["k"] + kw.get("n_shared", 0)) * kw["F"] * 4
     else:
         with pytest.raises(B.MoeError) as ei:
             B.Context(**kw)
@@ -61,7 +64,7 @@ def test_create_validates_shape(kw, status):
 def test_create_rejects_unknown_dtype_and_null():
     L = B.lib()
     h = ctypes.c_void_p()
-    shape = B.MoeShape(64, 64, 256, 4, 2, 7, 0)
+    shape = B.MoeShape(64, 64, 256, 4, 2, 7, 0, 0)
     assert L.moe_create(ctypes.byref(h), ctypes.byref(shape)) == B.MOE_ERR_DTYPE
     assert L.moe_create(None, ctypes.byref(shape)) == B.MOE_ERR_NULL
     assert L.moe_destroy(None) == B.MOE_ERR_NULL
@@ -129,3 +132,4 @@ def test_policy_row_count_matches_the_oracle_mask():
             mask, R = O.refresh_mask(s, pol.kind, pol.step_t, pol.stride_n, pol.n_units)
             assert R == int(mask.sum())
             assert pol.refreshed_pairs(T, k) == R, (T, k, pol)
+            assert pol.refreshed_pairs(T, k, 2) == R + 2 * T      # shared slots: every token, every step

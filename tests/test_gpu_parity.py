@@ -432,6 +432,154 @@ def test_layer_config3_xl_full_size_sampled(layer):
     sampled_layer_check(g, st, li, 2, f"cfg3 layer {layer}", seed=layer)
 
 
+# ----------------------------------------------------------------------------- shared experts
+def shared_reference_tables(ref, E, n_shared):
+    """Per-pair arrays of a layer with shared experts, from the oracle's routed result: the shared
+    slots follow the k routed ones (expert E+s, score 1, always refreshed), and the permutation is
+    the oracle's own stable sort run on those extended arrays."""
+    T = ref.idx.shape[0]
+    idx = np.concatenate([ref.idx, np.broadcast_to(E + np.arange(n_shared, dtype=np.int32), (T, n_shared))], axis=1)
+    s = np.concatenate([ref.s, np.ones((T, n_shared))], axis=1)
+    mask = np.concatenate([ref.mask, np.ones((T, n_shared), np.uint8)], axis=1)
+    counts, offsets, perm, inv = O.dispatch(idx, mask, E + n_shared)
+    return idx, s, mask, counts, offsets, perm, inv
+
+
+def check_shared_tables(g, ref, E, n_shared, with_mask):
+    idx, s, mask, counts, offsets, perm, inv = shared_reference_tables(ref, E, n_shared)
+    R = perm.shape[0]
+    np.testing.assert_array_equal(G.to_np(g.buf.expert_idx), idx)
+    np.testing.assert_allclose(G.to_np(g.buf.scores), s, rtol=5e-5)
+    np.testing.assert_array_equal(G.to_np(g.buf.scores)[:, -n_shared:], 1.0)
+    if with_mask:
+        np.testing.assert_array_equal(G.to_np(g.buf.mask), mask)
+        assert int(g.buf.n_refresh.item()) == R == ref.R + n_shared * idx.shape[0]
+    np.testing.assert_array_equal(G.to_np(g.buf.counts), counts)
+    np.testing.assert_array_equal(G.to_np(g.buf.offsets), offsets)
+    np.testing.assert_array_equal(G.to_np(g.buf.perm)[:R], perm)
+    np.testing.assert_array_equal(G.to_np(g.buf.inv).reshape(inv.shape), inv)
+    return offsets, perm, inv
+
+
+@pytest.mark.parametrize("dtype,T,d,E,F,k,n_shared", [("f32", 64, 64, 4, 256, 2, 2), ("f32", 77, 64, 5, 128, 1, 1),
+                                                     ("bf16", 1000, 128, 8, 512, 2, 2), ("bf16", 333, 64, 6, 256, 3, 3)])
+@pytest.mark.parametrize("fused", [False, True])
+def test_shared_experts_synchronous_layer_full_parity(dtype, T, d, E, F, k, n_shared, fused):
+    """A layer with shared experts (Section 5.1, "Models and Datasets"; supplement, "More details of
+    MoE"): routed tables, the shared slots, every h row and y against the oracle."""
+    x, Wg, bg, W1, b1, W2, b2 = G.small_inputs(71, T, d, E + n_shared, F, dtype, bias=True, w_std=0.03)
+    Wg, bg = Wg[:E].copy(), bg[:E].copy()
+    say(f"shared experts: {dtype} T={T} d={d} E={E}+{n_shared} F={F} k={k} fused={fused}")
+    z = O.router_logits(x, Wg, bg)
+    assert G.topk_margin(z, k) >= 1e-5
+    g = G.GpuLayer(x, Wg, bg, W1, b1, W2, b2, k, dtype, n_shared=n_shared)
+    y = G.to_np(g.forward(fuse_gather=fused))
+    ref = O.moe_layer(x, Wg, bg, W1, b1, W2, b2, k, n_shared=n_shared)
+    offsets, perm, inv = check_shared_tables(g, ref, E, n_shared, with_mask=False)
+    # every packed row, shared experts' rows included, through the oracle's per-row routine
+    xp = x[perm // (k + n_shared)]
+    if not fused:
+        np.testing.assert_array_equal(G.to_np(g.buf.x_packed)[:perm.shape[0]], xp)
+    h_ref = O.expert_ffn(xp, offsets, np.arange(E + n_shared), W1, b1, W2, b2)
+    G.assert_close_storage(G.to_np(g.buf.h_packed)[:perm.shape[0]], h_ref, dtype, "h rows")
+    G.assert_close_storage(y, ref.y, dtype, "y with shared experts", wide_range=True)
+    share = np.linalg.norm(ref.y_shared) / np.linalg.norm(ref.y)
+    say(f"  shared experts carry {100 * share:.0f}% of |y|")
+    assert share > 0.2                      # the check would notice a missing shared term
+
+
+def test_shared_experts_stay_fresh_under_conditional_refresh():
+    """Two steps with caches: the routed pairs follow the policy, the shared experts are recomputed
+    in every step (supplement, "Influence of Shared Experts") and never enter the caches."""
+    dtype, T, d, E, F, k, n_shared = "bf16", 1024, 128, 8, 256, 2, 2
+    x0, Wg, bg, W1, b1, W2, b2 = G.small_inputs(73, T, d, E + n_shared, F, dtype, bias=True, w_std=0.03)
+    Wg, bg = Wg[:E].copy(), bg[:E].copy()
+    r = np.random.Generator(np.random.PCG64(74))
+    x1 = WL.to_storage(x0 + np.float32(0.2) * r.standard_normal(x0.shape, dtype=np.float32), dtype)
+    for x in (x0, x1):
+        assert G.topk_margin(O.router_logits(x, Wg, bg), k) >= 1e-5
+    g = G.GpuLayer(x0, Wg, bg, W1, b1, W2, b2, k, dtype, with_cache=True, n_shared=n_shared)
+    x1_dev = G.to_dev(x1, dtype)
+    kc = k + n_shared
+    H0 = np.zeros((T, k, d)); S0 = np.zeros((T, k))
+    r0 = O.moe_layer(x0, Wg, bg, W1, b1, W2, b2, k, n_shared=n_shared, H_cache=H0, S_cache=S0)
+    policies = [B.Policy(B.REFRESH_ALG4, step_t=1, stride_n=2), B.Policy(B.REFRESH_ALG4, step_t=2, stride_n=2),
+                B.Policy(B.REFRESH_NONE), B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=T // 4),
+                B.Policy(B.REFRESH_FRACTION_PAIR, n_units=T + T // 2),
+                B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=T // 2, use_fresh_scores=True)]
+    for fused in (False, True):
+        for pol in policies:
+            g.buf.H_cache.fill_(7.0); g.buf.S_cache.fill_(7.0)
+            y0 = G.to_np(g.forward(B.Policy(B.REFRESH_ALL), fuse_gather=fused))
+            G.assert_close_storage(y0, r0.y, dtype, "step0 y", wide_range=True)
+            Hc0, Sc0 = G.to_np(g.buf.H_cache).copy(), G.to_np(g.buf.S_cache).copy()
+            # shared slots of the caches are never written
+            assert (Hc0[:, k:] == 7.0).all() and (Sc0[:, k:] == 7.0).all()
+            G.assert_close_storage(Hc0[:, :k].reshape(T * k, d), H0.reshape(T * k, d), dtype, "step0 cache")
+            y1 = G.to_np(g.forward(pol, x=x1_dev, fuse_gather=fused))
+            H, S = H0.copy(), S0.copy()
+            r1 = O.moe_layer(x1, Wg, bg, W1, b1, W2, b2, k, n_shared=n_shared, policy=pol.kind, step_t=pol.step_t,
+                             stride_n=pol.stride_n, n_units=pol.n_units, H_cache=H, S_cache=S,
+                             use_fresh_scores=pol.use_fresh_scores)
+            s_gpu = G.to_np(g.buf.scores)[:, :k].astype(np.float64)
+            m_from_gpu_scores, R = O.refresh_mask(s_gpu, pol.kind, pol.step_t, pol.stride_n, pol.n_units)
+            m_gpu = G.to_np(g.buf.mask)
+            np.testing.assert_array_equal(m_gpu[:, :k], m_from_gpu_scores, err_msg=str(pol))
+            np.testing.assert_array_equal(m_gpu[:, k:], 1)
+            assert int(g.buf.n_refresh.item()) == R + n_shared * T == pol.refreshed_pairs(T, k, n_shared)
+            if np.array_equal(m_gpu[:, :k], r1.mask):
+                check_shared_tables(g, r1, E, n_shared, with_mask=True)
+                G.assert_close_storage(y1, r1.y, dtype, f"step1 y {pol}", wide_range=True)
+                G.assert_close_storage(G.to_np(g.buf.H_cache)[:, :k].reshape(T * k, d), H.reshape(T * k, d), dtype,
+                                       "cache")
+                np.testing.assert_allclose(G.to_np(g.buf.S_cache)[:, :k], S, rtol=5e-5)
+            else:
+                assert pol.kind in (B.REFRESH_FRACTION_TOKEN, B.REFRESH_FRACTION_PAIR)
+                assert (m_gpu[:, :k] != r1.mask).sum() <= 2 * k
+            keep = m_gpu == 0
+            np.testing.assert_array_equal(G.to_np(g.buf.H_cache)[keep], Hc0[keep])
+            np.testing.assert_array_equal(G.to_np(g.buf.S_cache)[keep], Sc0[keep])
+            assert (G.to_np(g.buf.H_cache)[:, k:] == 7.0).all()
+            say(f"  fused={fused} {pol}: R={R}+{n_shared * T}")
+
+
+def test_shared_experts_config3_xl_full_size_sampled():
+    """DiT-MoE-XL shape with its two shared experts at full size: integer stages in full, y on
+    sampled tokens (routed rows by the oracle's per-row routine, shared part by its dense definition)."""
+    n_shared = 2
+    li, z = G.pick_layer(3, n_shared=n_shared)
+    c, k = li.cfg, li.cfg.k
+    E, T = c.E, c.T
+    say(f"config 3 with {n_shared} shared experts, seed {li.seed}")
+    g = G.GpuLayer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, k, "bf16", n_shared=n_shared)
+    g.forward(fuse_gather=True)
+    idx = O.topk(z, k)
+    _, s = O.scores(z, idx)
+
+    class RoutedOnly:                       # the fields shared_reference_tables reads
+        pass
+    ref = RoutedOnly()
+    ref.idx, ref.s, ref.mask, ref.R = idx, s, np.ones((T, k), np.uint8), T * k
+    offsets, perm, inv = check_shared_tables(g, ref, E, n_shared, with_mask=False)
+    r = np.random.Generator(np.random.PCG64(5))
+    toks = np.sort(r.choice(T, size=48, replace=False)).astype(np.int32)
+    kc = k + n_shared
+    rows = np.unique(inv[toks][:, :k].reshape(-1)).astype(np.int32)
+    xp = li.x[perm // kc]
+    h_ref = O.expert_ffn(xp, offsets, np.arange(E + n_shared), li.W1, None, li.W2, None, rows_sel=rows)
+    G.assert_close_storage(G.to_np(g.buf.h_packed)[rows], h_ref, "bf16", "routed h rows")
+    h_sparse = np.zeros((perm.shape[0], c.d))
+    h_sparse[rows] = h_ref
+    y_routed = O.combine(h_sparse, inv[:, :k].copy(), s, None, tokens_sel=toks)
+    y_shared = O.shared_experts(li.x[toks], li.W1[E:], None, li.W2[E:], None)
+    G.assert_close_storage(G.to_np(g.buf.y)[toks], y_routed + y_shared, "bf16", "y tokens", wide_range=True)
+    # the shared experts' own rows: one dense FFN each
+    for e in range(n_shared):
+        rows_s = inv[toks][:, k + e]
+        one = O.shared_experts(li.x[toks], li.W1[E + e:E + e + 1], None, li.W2[E + e:E + e + 1], None)
+        G.assert_close_storage(G.to_np(g.buf.h_packed)[rows_s], one, "bf16", f"shared expert {e} rows", wide_range=True)
+
+
 # ----------------------------------------------------------------------------- conditional refresh, two steps
 def run_two_steps(T, cfg=4, fractions=(0.25, 0.5, 0.75, 1.0), sample=None):
     li, _ = G.pick_layer(cfg, T=T)

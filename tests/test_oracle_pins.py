@@ -389,6 +389,83 @@ def test_partial_refresh_blends_fresh_and_cached_pairs():
         O.moe_layer(x1, *w, k=k, policy=O.REFRESH_ALG4, step_t=1, stride_n=2)
 
 
+# ----------------------------------------------------------------------------- shared experts
+def shared_weights(seed, S, d, F, bias=True):
+    r = rng(seed)
+    W1s = r.standard_normal((S, F, d), dtype=np.float32) * np.float32(0.2)
+    W2s = r.standard_normal((S, d, F), dtype=np.float32) * np.float32(0.2)
+    b1s = r.standard_normal((S, F), dtype=np.float32) * np.float32(0.1) if bias else None
+    b2s = r.standard_normal((S, d), dtype=np.float32) * np.float32(0.1) if bias else None
+    return W1s, b1s, W2s, b2s
+
+
+def test_shared_experts_closed_forms():
+    # d = F = 1, unit weights: each shared expert is gelu itself, so S of them give S * gelu(x)
+    xs = np.array([[0.0], [1.0], [-1.0], [2.0]], np.float32)
+    ones = np.ones((3, 1, 1), np.float32)
+    out = O.shared_experts(xs, ones, None, ones, None)[:, 0]
+    np.testing.assert_allclose(out, 3 * np.array([0.0, 0.8413447460685429, -0.15865525393145707,
+                                                  1.9544997361036416]), rtol=1e-14, atol=1e-16)
+    # zero weights leave the sum of the output biases; a bias on the hidden layer goes through gelu
+    W1s, b1s, W2s, b2s = shared_weights(31, 2, 6, 10)
+    x = rng(32).standard_normal((9, 6), dtype=np.float32)
+    out = O.shared_experts(x, W1s * 0, b1s * 0, W2s * 0, b2s)
+    np.testing.assert_allclose(out, np.broadcast_to(b2s.astype(np.float64).sum(axis=0), (9, 6)), rtol=1e-15)
+    W2row = np.zeros((1, 1, 2), np.float32); W2row[0, 0] = [1.0, 0.0]
+    out = O.shared_experts(np.zeros((1, 1), np.float32), np.zeros((1, 2, 1), np.float32),
+                           np.array([[1.0, -1.0]], np.float32), W2row, None)
+    np.testing.assert_allclose(out, [[0.8413447460685429]], rtol=1e-14)   # picks gelu(b1[0]) only
+
+
+def test_shared_experts_against_the_segmented_c_routine_and_a_scalar_loop():
+    # the dense numpy definition against (a) the C per-row routine run with one segment of all
+    # rows per shared expert, (b) scalar Python loops with math.erf
+    W1s, b1s, W2s, b2s = shared_weights(33, 2, 7, 13)
+    T, d, F = 11, 7, 13
+    x = rng(34).standard_normal((T, d), dtype=np.float32)
+    out = O.shared_experts(x, W1s, b1s, W2s, b2s)
+    via_c = sum(O.expert_ffn(x, [0, T], [e], W1s, b1s, W2s, b2s) for e in range(2))
+    np.testing.assert_allclose(out, via_c, rtol=1e-12, atol=1e-14)
+    for i in (0, 5, 10):
+        for c in (0, 3, 6):
+            acc = 0.0
+            for e in range(2):
+                acc += float(b2s[e, c])
+                for f in range(F):
+                    u = float(b1s[e, f]) + sum(float(W1s[e, f, q]) * float(x[i, q]) for q in range(d))
+                    acc += float(W2s[e, c, f]) * 0.5 * u * (1.0 + math.erf(u / math.sqrt(2.0)))
+            assert abs(out[i, c] - acc) <= 1e-12 * max(1.0, abs(acc))
+
+
+def test_layer_with_shared_experts_adds_them_ungated_and_always_fresh():
+    x0, x1, w = two_steps(23)
+    Wg, bg, W1, b1, W2, b2 = w
+    T, d, k, E = x0.shape[0], x0.shape[1], 2, Wg.shape[0]
+    W1s, b1s, W2s, b2s = shared_weights(35, 2, d, W1.shape[1])
+    cat = lambda a, b: np.concatenate([a, b], axis=0)
+    wS = (Wg, bg, cat(W1, W1s), cat(b1, b1s), cat(W2, W2s), cat(b2, b2s))
+    plain = O.moe_layer(x0, *w, k=k)
+    both = O.moe_layer(x0, *wS, k=k, n_shared=2)
+    # routing is untouched; y grows by the plain sum of the two dense FFNs (library matmuls)
+    np.testing.assert_array_equal(both.idx, plain.idx); np.testing.assert_array_equal(both.s, plain.s)
+    add = np_expert(x0, W1s[0], b1s[0], W2s[0], b2s[0]) + np_expert(x0, W1s[1], b1s[1], W2s[1], b2s[1])
+    np.testing.assert_allclose(both.y, plain.y + add, rtol=1e-12, atol=1e-13)
+    # a shared expert is a routed expert that every token selects with score 1: with one routed
+    # expert and k = 1 the softmax score is 1, so sharing that expert's weights doubles the output
+    one = O.moe_layer(x0, Wg[:1], bg[:1], W1[:1], b1[:1], W2[:1], b2[:1], k=1)
+    two = O.moe_layer(x0, Wg[:1], bg[:1], cat(W1[:1], W1[:1]), cat(b1[:1], b1[:1]), cat(W2[:1], W2[:1]),
+                      cat(b2[:1], b2[:1]), k=1, n_shared=1)
+    np.testing.assert_allclose(two.y, 2.0 * one.y, rtol=1e-12, atol=1e-14)
+    # staleness stays with the routed experts: with nothing refreshed the routed part is the
+    # cache's, the shared part is this step's
+    H = np.zeros((T, k, d)); S = np.zeros((T, k))
+    r0 = O.moe_layer(x0, *wS, k=k, n_shared=2, H_cache=H, S_cache=S)
+    r1 = O.moe_layer(x1, *wS, k=k, n_shared=2, policy=O.REFRESH_NONE, H_cache=H, S_cache=S)
+    assert r1.R == 0
+    add1 = np_expert(x1, W1s[0], b1s[0], W2s[0], b2s[0]) + np_expert(x1, W1s[1], b1s[1], W2s[1], b2s[1])
+    np.testing.assert_allclose(r1.y, (r0.y - r0.y_shared) + add1, rtol=1e-11, atol=1e-13)
+
+
 # ----------------------------------------------------------------------------- expert-parallel layout
 def test_ep_receive_layout_and_segmented_ffn():
     r = rng(21)
