@@ -41,6 +41,10 @@ def main():
     ap.add_argument("--n-shared", type=int, default=0,
                     help="add this many shared experts (always-fresh dense FFNs; DiT-MoE carries 2) to every layer; "
                          "the headline workload has none")
+    ap.add_argument("--schedule", choices=["sync", "interweaved", "displaced"], default="sync",
+                    help="step-level schedule of every layer (Algorithms 1-3); the headline workload is the synchronous "
+                         "layer.  The asynchronous ones read the persistent combine buffer and run the expert call "
+                         "whose results the next step collects on a second stream")
     ap.add_argument("--eager", action="store_true", help="launch from Python every step instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -79,16 +83,38 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
 
-    def one_step():
+    deferred = None
+    if args.schedule != "sync":
+        from paper_2411_16786_amd import schedule as SCH
+        deferred = torch.cuda.Stream()
+        side_ws = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
         for L in layers:
-            B.moe_layer_forward(ctx, L["buf"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None,
-                                fuse_gather=not args.packed_dispatch)
+            L["state"] = SCH.LayerState(ctx, dev, displaced=(args.schedule == "displaced"), workspace=workspace,
+                                        side_workspace=side_ws)
+            # one synchronous step fills the persistent buffers (and, for displaced, leaves a dispatch to wait on)
+            SCH.moe_layer_step(SCH.SYNC, L["state"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None)
+        torch.cuda.synchronize()
+
+    def one_step():
+        if deferred is None:
+            for L in layers:
+                B.moe_layer_forward(ctx, L["buf"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None,
+                                    fuse_gather=not args.packed_dispatch)
+            return
+        for L in layers:
+            SCH.moe_layer_step(args.schedule, L["state"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None,
+                               side_stream=deferred)
+        torch.cuda.current_stream().wait_stream(deferred)      # the step ends when its deferred expert calls have
+        for L in layers:
+            L["state"].commit_done = None
+            L["buf"] = L["state"].buf                      # where this step's outputs are
 
     # ---- optional HIP graph of one step (the launch sequence is static)
     graph = None
     one_step()
     torch.cuda.synchronize()
-    if not args.eager:
+    # (displaced alternates between two sets of layer buffers from step to step: launched eagerly)
+    if not args.eager and args.schedule != "displaced":
         graph = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -250,7 +276,7 @@ def main():
         "config": {"workload": "configs[2]: DiT-MoE-XL-shaped layer x 28 (T=4096, d=1152, E=8, top-2, F=4608)"
                                + (f" + {n_shared} shared experts per layer" if n_shared else ""),
                    "layers": n_layers, "tokens": T, "launch": "eager" if graph is None else "hipGraph replay",
-                   "refresh": "full (synchronous layer)"},
+                   "refresh": "full (synchronous layer)", "schedule": args.schedule},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "stages": stages,

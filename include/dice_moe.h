@@ -180,6 +180,29 @@ int moe_expert_ffn_rows(moe_ctx* ctx, const void* x, const int32_t* row_pairs,
                         int32_t max_rows, const void* W1, const float* b1, const void* W2,
                         const float* b2, void* h_packed, void* workspace, void* stream);
 
+/* Expert FFN whose results go straight into the persistent combine buffer, for the asynchronous
+ * schedules (Algorithm 3, "async_combine" of the expert outputs, waited for in the next step;
+ * Algorithm 2 likewise; Section 4.1: only the combined results are buffered for the next step).
+ * The h row of packed row r is written to H_buffer[out_pairs[r]] (a row per pair id, the layout of
+ * moe_combine's H_cache) instead of a packed buffer, and S_buffer[p] = scores[p] for the routed
+ * slots of every pair with mask[p] != 0 (all of them if mask is NULL): after the call the buffers
+ * hold this step's results for the refreshed pairs and the older ones for the rest, which is what
+ * moe_combine reads in the next step when it is given a mask that refreshes nothing.
+ *   in : x_rows: the packed rows (row_pairs NULL) or x[T][d] read through row_pairs as in
+ *        moe_expert_ffn_rows; out_pairs[>= seg_offsets[n_segments]] (device), the pair id of
+ *        each packed row (moe_dispatch's perm), every entry in 0..T_max*k-1 and distinct;
+ *        scores[T][k], mask[T][k] or NULL: those of the step the packed rows were dispatched in;
+ *        the other arguments as for moe_expert_ffn
+ *   io : H_buffer[T_max*k][d] (dtype), S_buffer[T_max*k] float; rows and scores of pairs that
+ *        are not named stay as they are
+ * The caller orders this call after the moe_combine that still reads the old buffer contents. */
+int moe_expert_ffn_commit(moe_ctx* ctx, const void* x_rows, const int32_t* row_pairs,
+                          const int32_t* out_pairs, const int32_t* seg_offsets,
+                          const int32_t* seg_expert, int32_t n_segments, int32_t max_rows,
+                          const void* W1, const float* b1, const void* W2, const float* b2,
+                          const float* scores, const uint8_t* mask, int32_t T, void* H_buffer,
+                          float* S_buffer, void* workspace, void* stream);
+
 /* Combine + scale + cache blend (Algorithm 1 combine/scale; Algorithm 4 "reuse stale h"):
  *   y_i = sum_{j=0..k-1} s*_ij h*_ij   accumulated in float in slot order,
  * where a refreshed pair takes h_packed[inv[p]] and scores[p] and writes both through to

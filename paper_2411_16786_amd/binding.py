@@ -26,7 +26,7 @@ MOE_ERR_WORKSPACE, MOE_ERR_CACHE_COLD, MOE_ERR_HIP = -5, -6, -7
 
 EXPORTS = ["moe_create", "moe_destroy", "moe_workspace_bytes", "moe_last_error", "moe_status_string",
            "moe_gate", "moe_conditional_refresh", "moe_dispatch", "moe_expert_ffn", "moe_expert_ffn_rows",
-           "moe_combine", "moe_ep_segments"]
+           "moe_expert_ffn_commit", "moe_combine", "moe_ep_segments"]
 
 
 class MoeShape(ctypes.Structure):
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.moe_dispatch.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn_rows.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.moe_expert_ffn_commit.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.moe_combine.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
         L.moe_ep_segments.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         for name in EXPORTS:
@@ -193,6 +194,19 @@ class Context:
                                               max_rows, _ptr(W1, self.torch_dtype), _ptr(b1, torch.float32),
                                               _ptr(W2, self.torch_dtype), _ptr(b2, torch.float32),
                                               _ptr(h_packed, self.torch_dtype), _ptr(workspace), _stream()))
+
+    def moe_expert_ffn_commit(self, x_rows, row_pairs, out_pairs, seg_offsets, seg_expert, max_rows, W1, b1, W2, b2,
+                              scores, mask, H_buffer, S_buffer, workspace):
+        n_seg = seg_expert.shape[0]
+        T = scores.shape[0]
+        self._check(lib().moe_expert_ffn_commit(self._h, _ptr(x_rows, self.torch_dtype), _ptr(row_pairs, torch.int32),
+                                                _ptr(out_pairs, torch.int32), _ptr(seg_offsets, torch.int32),
+                                                _ptr(seg_expert, torch.int32), n_seg, max_rows,
+                                                _ptr(W1, self.torch_dtype), _ptr(b1, torch.float32),
+                                                _ptr(W2, self.torch_dtype), _ptr(b2, torch.float32),
+                                                _ptr(scores, torch.float32), _ptr(mask, torch.uint8), T,
+                                                _ptr(H_buffer, self.torch_dtype), _ptr(S_buffer, torch.float32),
+                                                _ptr(workspace), _stream()))
 
     def moe_combine(self, h_packed, inv, scores, mask, H_cache, S_cache, use_fresh_scores, y):
         T = scores.shape[0]

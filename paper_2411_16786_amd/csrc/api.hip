@@ -187,7 +187,7 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const u
 static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, const int32_t* row_pairs,
                              const int32_t* seg_offsets, const int32_t* seg_expert, int32_t n_segments,
                              int32_t max_rows, const void* W1, const float* b1, const void* W2, const float* b2,
-                             void* h_packed, void* workspace, void* stream)
+                             void* h_packed, const int32_t* out_pairs, void* workspace, void* stream)
 {
     const moe_shape& s = ctx->shape;
     if (n_segments < 1 || n_segments > 1024)
@@ -204,7 +204,7 @@ static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, 
     }
     return hip_result(ctx,
                       launch_expert_ffn(is_bf16(ctx), x_rows, row_pairs, slots(ctx), seg_offsets, seg_expert, n_segments,
-                                        max_rows, s.d, s.F, W1, b1, W2, b2, h_packed, workspace,
+                                        max_rows, s.d, s.F, W1, b1, W2, b2, h_packed, out_pairs, workspace,
                                         static_cast<hipStream_t>(stream)),
                       who);
 }
@@ -217,7 +217,7 @@ int moe_expert_ffn(moe_ctx* ctx, const void* x_packed, const int32_t* seg_offset
 {
     if (!ctx) return MOE_ERR_NULL;
     return expert_ffn_common(ctx, "moe_expert_ffn", x_packed, nullptr, seg_offsets, seg_expert, n_segments, max_rows, W1,
-                             b1, W2, b2, h_packed, workspace, stream);
+                             b1, W2, b2, h_packed, nullptr, workspace, stream);
 }
 
 int moe_expert_ffn_rows(moe_ctx* ctx, const void* x, const int32_t* row_pairs, const int32_t* seg_offsets,
@@ -228,7 +228,26 @@ int moe_expert_ffn_rows(moe_ctx* ctx, const void* x, const int32_t* row_pairs, c
     if (!ctx) return MOE_ERR_NULL;
     if (!row_pairs) return fail(ctx, MOE_ERR_NULL, "moe_expert_ffn_rows: row_pairs is null");
     return expert_ffn_common(ctx, "moe_expert_ffn_rows", x, row_pairs, seg_offsets, seg_expert, n_segments, max_rows, W1,
-                             b1, W2, b2, h_packed, workspace, stream);
+                             b1, W2, b2, h_packed, nullptr, workspace, stream);
+}
+
+int moe_expert_ffn_commit(moe_ctx* ctx, const void* x_rows, const int32_t* row_pairs, const int32_t* out_pairs,
+                          const int32_t* seg_offsets, const int32_t* seg_expert, int32_t n_segments, int32_t max_rows,
+                          const void* W1, const float* b1, const void* W2, const float* b2, const float* scores,
+                          const uint8_t* mask, int32_t T, void* H_buffer, float* S_buffer, void* workspace,
+                          void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (int rc = check_T(ctx, T)) return rc;
+    if (!out_pairs || !scores || !H_buffer || !S_buffer)
+        return fail(ctx, MOE_ERR_NULL, "moe_expert_ffn_commit: null pointer");
+    if (int rc = expert_ffn_common(ctx, "moe_expert_ffn_commit", x_rows, row_pairs, seg_offsets, seg_expert, n_segments,
+                                   max_rows, W1, b1, W2, b2, H_buffer, out_pairs, workspace, stream))
+        return rc;
+    return hip_result(ctx,
+                      launch_commit_scores(scores, mask, T, slots(ctx), ctx->shape.k, S_buffer,
+                                           static_cast<hipStream_t>(stream)),
+                      "moe_expert_ffn_commit");
 }
 
 int moe_combine(moe_ctx* ctx, const void* h_packed, const int32_t* inv, const float* scores, const uint8_t* mask,

@@ -130,4 +130,23 @@ hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, c
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void commit_scores_kernel(const float* __restrict__ scores,
+                                                           const uint8_t* __restrict__ mask, int n_pairs, int k,
+                                                           int k_cached, float* __restrict__ S_buffer)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n_pairs || p % k >= k_cached) return;
+    if (mask == nullptr || mask[p] != 0) S_buffer[p] = scores[p];
+}
+
+hipError_t launch_commit_scores(const float* scores, const uint8_t* mask, int T_tok, int k, int k_cached,
+                                float* S_buffer, hipStream_t stream)
+{
+    const int n_pairs = T_tok * k;
+    if (n_pairs == 0) return hipSuccess;
+    hipLaunchKernelGGL(commit_scores_kernel, dim3((n_pairs + 255) / 256), dim3(256), 0, stream, scores, mask, n_pairs, k,
+                       k_cached, S_buffer);
+    return hipGetLastError();
+}
+
 }  // namespace dicemoe

@@ -33,7 +33,8 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
                                                                  const int32_t* __restrict__ seg_offsets,
                                                                  const int32_t* __restrict__ seg_expert, int n_seg,
                                                                  int n_tiles_n, int m_tiles_max,
-                                                                 const int32_t* __restrict__ row_index, int row_div)
+                                                                 const int32_t* __restrict__ row_index, int row_div,
+                                                                 const int32_t* __restrict__ out_index)
 {
     constexpr int BK = 64;
     constexpr int CH = BK / 8;          // 16-byte chunks per tile row
@@ -164,7 +165,8 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
     read_bias_groups<TN>(bias_lds, lane, bias_groups);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-        store_slab<TN, GELU>(acc[i], region, bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
+        store_slab<TN, GELU>(acc[i], region, bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane,
+                             out_index);
 }
 
 // float path (small workloads): 64x64 tile, depth 16, each thread a 4x4 block, plain FMAs in a
@@ -175,7 +177,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
                                                            int N, int K, const int32_t* __restrict__ seg_offsets,
                                                            const int32_t* __restrict__ seg_expert, int n_seg,
                                                            int n_tiles_n, const int32_t* __restrict__ row_index,
-                                                           int row_div)
+                                                           int row_div, const int32_t* __restrict__ out_index)
 {
     constexpr int BM = 64, BN = 64, BK = 16;
     __shared__ float As[BK][BM + 4];
@@ -227,13 +229,15 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
     for (int i = 0; i < 4; ++i) {
         const int r = row0 + ty * 4 + i;
         if (r >= row_end) continue;
+        const int r_out = out_index ? out_index[r] : r;      // scatter: the row out_index names
+        if (r_out < 0) continue;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + tx * 4 + j;
             if (n >= N) continue;
             float val = acc[i][j] + (bias ? bias[static_cast<size_t>(e) * N + n] : 0.f);
             if (GELU) val = gelu_erf(val);
-            C[static_cast<size_t>(r) * N + n] = val;
+            C[static_cast<size_t>(r_out) * N + n] = val;
         }
     }
 }
@@ -241,7 +245,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
 template <int BM, int BN, int OCC, bool XCD, bool GELU>
 static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                    const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
-                                   hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1)
+                                   hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1,
+                                   const int32_t* out_index = nullptr)
 {
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
@@ -249,20 +254,22 @@ static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bi
     hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, OCC, XCD, GELU>), dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n),
                        dim3(256), 0, stream, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias,
                        static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index,
-                       row_div);
+                       row_div, out_index);
     return hipGetLastError();
 }
 
 template <bool GELU>
 static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                   const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
-                                  hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1)
+                                  hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1,
+                                  const int32_t* out_index = nullptr)
 {
     const int n_tiles_n = (N + 63) / 64;
     const int m_tiles = (max_rows + 63) / 64 + n_seg;
     hipLaunchKernelGGL((ffn_gemm_f32_kernel<GELU>), dim3(static_cast<unsigned>(m_tiles) * n_tiles_n), dim3(256), 0,
                        stream, static_cast<const float*>(A), static_cast<const float*>(W), bias,
-                       static_cast<float*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, row_index, row_div);
+                       static_cast<float*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, row_index, row_div,
+                       out_index);
     return hipGetLastError();
 }
 
@@ -284,7 +291,7 @@ template <bool GELU>
 static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
-                                        int row_div = 1)
+                                        int row_div = 1, const int32_t* out_index = nullptr)
 {
     constexpr int kComputeUnits = 256;
     // expected tiles: every segment ends in a partial row tile, half a tile on average
@@ -295,21 +302,21 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
     const bool fits_192 = (N + 191) / 192 * 192 * 8 <= N * 9;          // at most 1/8 of the columns computed in vain
     if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6) {
         if (K >= 256)
-            return launch_gemm_bf16_wide<4, 3, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
-        return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
+            return launch_gemm_bf16_wide<4, 3, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index);
+        return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index);
     }
     if (fits_192 && K >= 256 && tiles(128, 192) <= kComputeUnits && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
+        return launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index);
     if (fits_192 && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div);
+        return launch_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index);
     return launch_gemm_bf16<128, 128, 3, true, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
-                                                           row_div);
+                                                           row_div, out_index);
 }
 
 hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_index, int row_div,
                              const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
                              int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_packed,
-                             void* hidden, hipStream_t stream)
+                             const int32_t* out_index, void* hidden, hipStream_t stream)
 {
     if (max_rows == 0) return hipSuccess;
     hipError_t err;
@@ -317,12 +324,14 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_i
         err = launch_gemm_bf16_auto<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream,
                                           row_index, row_div);
         if (err != hipSuccess) return err;
-        return launch_gemm_bf16_auto<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream);
+        return launch_gemm_bf16_auto<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream,
+                                            nullptr, 1, out_index);
     }
     err = launch_gemm_f32<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
                                 row_div);
     if (err != hipSuccess) return err;
-    return launch_gemm_f32<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream);
+    return launch_gemm_f32<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream, nullptr, 1,
+                                  out_index);
 }
 
 }  // namespace dicemoe

@@ -139,13 +139,21 @@ __device__ __forceinline__ void read_bias_groups(const float* bias_lds, int lane
 template <int TN, bool GELU>
 __device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* region, const float4 (&bb)[TN][4],
                                            bf16_t* __restrict__ C, int N, int row_first, int row_end, int col_first,
-                                           int lane)
+                                           int lane, const int32_t* __restrict__ out_index)
 {
     constexpr int WN = TN * 32;
     constexpr int PITCH = WN * 2 + 16;            // bytes; keeps 16-byte alignment, staggers banks
     constexpr int CPR = WN / 8;                   // 16-byte chunks per slab row
     constexpr int NP = 32 * CPR / 64;             // 16-byte pieces per lane (32 * CPR = 128 TN: a whole number of wavefronts)
     const int m_local = lane & 31, h = lane >> 5;
+    // destination row of every piece this lane will store: the packed row itself, or (scatter) the row
+    // that out_index names for it; fetched first so that the arithmetic below covers the load
+    int dst_row[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int r = row_first + (lane + 64 * p) / CPR;
+        dst_row[p] = r < row_end ? (out_index ? out_index[r] : r) : -1;
+    }
     // phase 1: arithmetic and parking, no LDS read in between (nothing to wait for)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -169,9 +177,8 @@ __device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* reg
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         const int idx = lane + 64 * p;
-        const int r = row_first + idx / CPR;
         const int n = col_first + (idx % CPR) * 8;
-        if (r < row_end && n < N) *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(r) * N + n) = piece[p];
+        if (dst_row[p] >= 0 && n < N) *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(dst_row[p]) * N + n) = piece[p];
     }
     __builtin_amdgcn_wave_barrier();
 }

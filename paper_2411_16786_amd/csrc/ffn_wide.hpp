@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256, wide_occupancy(TM, TN, AST, WST)) void ffn_gem
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
     const int32_t* __restrict__ seg_expert, int n_seg, int n_tiles_n, int m_tiles_max,
-    const int32_t* __restrict__ row_index, int row_div)
+    const int32_t* __restrict__ row_index, int row_div, const int32_t* __restrict__ out_index)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     constexpr int WM = 32 * TM, WN = 32 * TN;
@@ -321,14 +321,15 @@ __global__ __launch_bounds__(256, wide_occupancy(TM, TN, AST, WST)) void ffn_gem
     read_bias_groups<TN>(bias_lds, lane, bias_groups);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-        store_slab<TN, GELU>(acc[i], region, bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane);
+        store_slab<TN, GELU>(acc[i], region, bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane,
+                             out_index);
 }
 
 template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG = 0>
 static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
-                                        int row_div = 1)
+                                        int row_div = 1, const int32_t* out_index = nullptr)
 {
     constexpr int BM = 64 * TM, BN = 64 * TN;
     auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, AST, WST, GELU, DIAG>;
@@ -346,7 +347,7 @@ static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const floa
     const int bands = (m_tiles + 7) / 8;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n), dim3(256), smem, stream,
                        static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, static_cast<bf16_t*>(C), N,
-                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index, row_div);
+                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index, row_div, out_index);
     return hipGetLastError();
 }
 

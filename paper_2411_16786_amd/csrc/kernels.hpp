@@ -32,11 +32,16 @@ hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, c
                           float* S_cache, int use_fresh, void* y, hipStream_t stream);
 
 // x_rows is the packed buffer (row_index == nullptr) or the token matrix with row_index[r] / row_div
-// naming the row that packed row r reads
+// naming the row that packed row r reads; the h row of packed row r is written to row r of h_out, or
+// to row out_index[r] when out_index is given (scatter into a buffer indexed by pair id)
 hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_index, int row_div,
                              const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
-                             int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_packed,
-                             void* hidden, hipStream_t stream);
+                             int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_out,
+                             const int32_t* out_index, void* hidden, hipStream_t stream);
+
+// S_buffer[p] = scores[p] for the routed slots (j < k_cached) of every pair with mask[p] != 0 (all if mask is null)
+hipError_t launch_commit_scores(const float* scores, const uint8_t* mask, int T_tok, int k, int k_cached,
+                                float* S_buffer, hipStream_t stream);
 
 hipError_t launch_ep_segments(const int32_t* recv_counts, int n_seg, int E_loc, int32_t* seg_offsets,
                               int32_t* seg_expert, hipStream_t stream);

@@ -100,6 +100,16 @@ def test_host_detectable_errors_return_before_any_launch():
     assert L.moe_expert_ffn_rows(h, one, None, one, one, 4, 8, one, None, one, None, one, one, None) == B.MOE_ERR_NULL
     assert b"row_pairs" in L.moe_last_error(h)
     assert L.moe_expert_ffn_rows(h, one, one, one, one, 4, 129, one, None, one, None, one, one, None) == B.MOE_ERR_SHAPE
+    # commit into the pair buffer: (ctx, x_rows, row_pairs, out_pairs, seg_offsets, seg_expert, n_seg, max_rows,
+    #                                 W1, b1, W2, b2, scores, mask, T, H_buffer, S_buffer, workspace, stream)
+    assert L.moe_expert_ffn_commit(h, one, None, None, one, one, 4, 8, one, None, one, None, one, None, 8, one, one,
+                                   one, None) == B.MOE_ERR_NULL                     # no out_pairs
+    assert L.moe_expert_ffn_commit(h, one, None, one, one, one, 4, 8, one, None, one, None, one, None, 8, one, None,
+                                   one, None) == B.MOE_ERR_NULL                     # no S_buffer
+    assert L.moe_expert_ffn_commit(h, one, None, one, one, one, 4, 8, one, None, one, None, one, None, 65, one, one,
+                                   one, None) == B.MOE_ERR_SHAPE                    # T > T_max
+    assert L.moe_expert_ffn_commit(h, one, None, one, one, one, 4, 8, one, None, one, None, one, None, 8, one, one,
+                                   None, None) == B.MOE_ERR_WORKSPACE
     assert L.moe_dispatch(h, None, one, None, 8, one, one, one, one, one, None, None) == B.MOE_ERR_NULL  # rows wanted, no x
     assert L.moe_ep_segments(h, one, 4, 8, one, one, None) == B.MOE_ERR_SHAPE     # E_loc > E
     # T = 0 launches nothing
