@@ -50,7 +50,22 @@
 #include <string.h>
 
 enum { ORACLE_REFRESH_ALL = 0, ORACLE_REFRESH_ALG4 = 1, ORACLE_REFRESH_FRACTION_TOKEN = 2,
-       ORACLE_REFRESH_FRACTION_PAIR = 3, ORACLE_REFRESH_NONE = 4 };
+       ORACLE_REFRESH_FRACTION_PAIR = 3, ORACLE_REFRESH_NONE = 4,
+       ORACLE_REFRESH_ALG4_HIGH = 5, ORACLE_REFRESH_ALG4_RANDOM = 6 };
+
+/* Counter-based draw for the "Random" row of the ablation table: the 32-bit avalanche step of
+ * MurmurHash3 (a published, public-domain bit mixer) applied to seed * 0x9E3779B9 + token, all in
+ * arithmetic modulo 2^32.  The draw belongs to the method's definition, so the GPU side carries
+ * its own copy of these five lines. */
+static uint32_t oracle_mix32(uint32_t seed, uint32_t token)
+{
+    uint32_t h = seed * 0x9E3779B9u + token;
+    h ^= h >> 16; h *= 0x85EBCA6Bu;
+    h ^= h >> 13; h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+uint32_t oracle_mix32_export(uint32_t seed, uint32_t token) { return oracle_mix32(seed, token); }
 
 /* ---- router: logits z[i,e] = sum_c x[i,c] Wg[e,c] + bg[e]  (Algorithm 1, router) ---- */
 void oracle_router_logits(const float* x, const float* Wg, const float* bg,
@@ -153,6 +168,25 @@ int oracle_refresh_mask(const double* s, int T, int k, int policy, int step_t, i
                 mask[(size_t)i * k + j] = (uint8_t)transmit;
                 R += transmit;
             }
+        return R;
+    case ORACLE_REFRESH_ALG4_HIGH:
+    case ORACLE_REFRESH_ALG4_RANDOM:
+        /* Ablation of which pair is deprioritised (Section 5.3, "Conditional Communication";
+         * ablation table rows "High Score" and "Random").  Algorithm 4 with another choice of the
+         * always-fresh slot: HIGH keeps the LOWEST-scoring activated expert (slot k-1) fresh and
+         * lets the higher-scoring ones go stale; RANDOM keeps one slot per token fresh, drawn
+         * from (seed = n_units, token). */
+        if (stride_n < 1 || step_t < 0) return -1;
+        for (int i = 0; i < T; ++i) {
+            const int fresh_slot = policy == ORACLE_REFRESH_ALG4_HIGH
+                                       ? k - 1
+                                       : (int)(oracle_mix32((uint32_t)n_units, (uint32_t)i) % (uint32_t)k);
+            for (int j = 0; j < k; ++j) {
+                const int transmit = (j == fresh_slot) || (step_t % stride_n == 0);
+                mask[(size_t)i * k + j] = (uint8_t)transmit;
+                R += transmit;
+            }
+        }
         return R;
     case ORACLE_REFRESH_FRACTION_TOKEN: {
         if (n_units < 0 || n_units > T) return -1;

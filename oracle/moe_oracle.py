@@ -23,6 +23,7 @@ _SRC = os.path.join(_HERE, "moe_oracle.c")
 _LIB = os.path.join(_HERE, "libmoe_oracle.so")
 
 REFRESH_ALL, REFRESH_ALG4, REFRESH_FRACTION_TOKEN, REFRESH_FRACTION_PAIR, REFRESH_NONE = range(5)
+REFRESH_ALG4_HIGH, REFRESH_ALG4_RANDOM = 5, 6      # ablation variants: which slot stays fresh
 
 
 def build(force: bool = False) -> str:
@@ -107,6 +108,14 @@ def refresh_mask(s, policy: int, step_t: int = 0, stride_n: int = 1, n_units: in
     if R < 0:
         raise ValueError("invalid refresh policy arguments")
     return mask, R
+
+
+def mix32(seed: int, token: int) -> int:
+    """The counter-based draw of REFRESH_ALG4_RANDOM (see ``moe_oracle.c``)."""
+    f = lib().oracle_mix32_export
+    f.restype = ctypes.c_uint32
+    f.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
+    return int(f(seed & 0xFFFFFFFF, token & 0xFFFFFFFF))
 
 
 def dispatch(idx, mask, E: int):

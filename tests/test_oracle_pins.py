@@ -298,6 +298,45 @@ def test_alg4_special_cases():
     assert mp.all() and Rp == 200
 
 
+def test_ablation_variants_of_algorithm_4():
+    # "High Score" / "Random" rows of the ablation table: same budget as Algorithm 4 (one slot per
+    # token on off-steps, everything on t mod n == 0), another choice of the slot that stays fresh
+    r = rng(41)
+    T, k = 4000, 3
+    s = -np.sort(-r.random((T, k)), axis=1)
+    for kind in (O.REFRESH_ALG4, O.REFRESH_ALG4_HIGH, O.REFRESH_ALG4_RANDOM):
+        on, R_on = O.refresh_mask(s, kind, step_t=4, stride_n=2, n_units=123)
+        assert R_on == T * k and on.all()
+        off, R_off = O.refresh_mask(s, kind, step_t=3, stride_n=2, n_units=123)
+        assert R_off == T and (off.sum(axis=1) == 1).all()
+    low, _ = O.refresh_mask(s, O.REFRESH_ALG4, 3, 2)
+    high, _ = O.refresh_mask(s, O.REFRESH_ALG4_HIGH, 3, 2)
+    assert low[:, 0].all() and high[:, k - 1].all()
+    # HIGH deprioritises high scores: the fresh pair is the token's smallest activated score, LOW's the largest
+    assert (s[high == 1] == s.min(axis=1)).all() and (s[low == 1] == s.max(axis=1)).all()
+    # RANDOM: the slot is a function of (seed, token) only, roughly uniform over the slots, and
+    # different seeds disagree on about (k-1)/k of the tokens
+    a, _ = O.refresh_mask(s, O.REFRESH_ALG4_RANDOM, 3, 2, n_units=123)
+    a2, _ = O.refresh_mask(s[::-1].copy(), O.REFRESH_ALG4_RANDOM, 5, 2, n_units=123)
+    np.testing.assert_array_equal(a, a2)                       # scores and step do not enter
+    b, _ = O.refresh_mask(s, O.REFRESH_ALG4_RANDOM, 3, 2, n_units=124)
+    share = a.mean(axis=0)
+    assert np.all(np.abs(share - 1.0 / k) < 0.03), share
+    differ = (a.argmax(axis=1) != b.argmax(axis=1)).mean()
+    assert abs(differ - (k - 1) / k) < 0.04
+    for i in (0, 1, 77, T - 1):
+        assert a[i].argmax() == O.mix32(123, i) % k
+    # the mixer: zero is its fixed point, it is a bijection (no collisions on a sample), and one
+    # flipped input bit flips about half of the output bits
+    assert O.mix32(0, 0) == 0
+    vals = {O.mix32(7, i) for i in range(20000)}
+    assert len(vals) == 20000
+    flips = [bin(O.mix32(7, i) ^ O.mix32(7, i ^ 1)).count("1") for i in range(2000)]
+    assert 14 < np.mean(flips) < 18
+    with pytest.raises(ValueError):
+        O.refresh_mask(s, O.REFRESH_ALG4_HIGH, 1, 0)
+
+
 def test_fraction_masks_against_brute_force_sort_and_nesting():
     r = rng(14)
     T, k = 257, 2
