@@ -45,6 +45,9 @@ def main():
                     help="step-level schedule of every layer (Algorithms 1-3); the headline workload is the synchronous "
                          "layer.  The asynchronous ones read the persistent combine buffer and run the expert call "
                          "whose results the next step collects on a second stream")
+    ap.add_argument("--workload", choices=["xl", "g"], default="xl",
+                    help="xl: DiT-MoE-XL shape x 28 layers (the headline workload); g: DiT-MoE-G shape (16 experts, "
+                         "d=1792) x 40 layers")
     ap.add_argument("--eager", action="store_true", help="launch from Python every step instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -60,7 +63,8 @@ def main():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
     dev = "cuda"
-    c = WL.CONFIGS[3]
+    wl_cfg = 3 if args.workload == "xl" else 6
+    c = WL.CONFIGS[wl_cfg]
     n_layers = args.layers or c.layers
     T, d, E, k, F = c.T, c.d, c.E, c.k, c.F
     n_shared = args.n_shared
@@ -68,18 +72,23 @@ def main():
 
     # ---- inputs: seeded on the host, uploaded once
     t_setup = time.time()
-    with ThreadPoolExecutor(max_workers=8) as pool:
-        host_layers = list(pool.map(lambda l: WL.make_layer(3, layer=l, n_shared=n_shared), range(n_layers)))
     ctx = B.Context(T, d, F, E, k, "bf16", n_shared=n_shared)
     workspace = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
     up = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(dev)
     layers = []
-    for li in host_layers:
-        buf = B.LayerBuffers(ctx, dev, workspace=workspace)
-        layers.append(dict(x=up(li.x), Wg=up(li.Wg), bg=torch.from_numpy(li.bg).to(dev), W1=up(li.W1),
-                           W2=up(li.W2), buf=buf))
-    cpu_layers = host_layers[:4]          # kept on the host for the oracle's timed sample
-    del host_layers
+    n_cpu = 4 if args.workload == "xl" else 2      # layers kept on the host for the oracle's timed sample
+    cpu_layers = []
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        for first in range(0, n_layers, 8):        # generated and uploaded eight layers at a time (host memory)
+            chunk = list(pool.map(lambda l: WL.make_layer(wl_cfg, layer=l, n_shared=n_shared),
+                                  range(first, min(first + 8, n_layers))))
+            for li in chunk:
+                buf = B.LayerBuffers(ctx, dev, workspace=workspace)
+                layers.append(dict(x=up(li.x), Wg=up(li.Wg), bg=torch.from_numpy(li.bg).to(dev), W1=up(li.W1),
+                                   W2=up(li.W2), buf=buf))
+            if first == 0:
+                cpu_layers = chunk[:n_cpu]
+            del chunk
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
 
@@ -184,7 +193,7 @@ def main():
                                  "frac_mfma": round(ffn_tflops / PEAK_BF16_TFLOPS, 4)})
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "bench_xl28_hbm_traffic.txt")
-    if os.path.exists(tpath):          # rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this same command (not live)
+    if os.path.exists(tpath) and args.workload == "xl" and n_shared == 0:          # rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this same command (not live)
         for line in open(tpath):
             if line.startswith("ffn_traffic_bytes_per_call:"):
                 traffic = int(line.split(":")[1].split()[0])
@@ -273,7 +282,9 @@ def main():
         "ms_per_layer": round(ms_per_step / n_layers, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[2]: DiT-MoE-XL-shaped layer x 28 (T=4096, d=1152, E=8, top-2, F=4608)"
+        "config": {"workload": ("configs[2]: DiT-MoE-XL-shaped layer x 28 (T=4096, d=1152, E=8, top-2, F=4608)"
+                                if args.workload == "xl" else
+                                f"DiT-MoE-G-shaped layer x {c.layers} (T={T}, d={d}, E={E}, top-{k}, F={F})")
                                + (f" + {n_shared} shared experts per layer" if n_shared else ""),
                    "layers": n_layers, "tokens": T, "launch": "eager" if graph is None else "hipGraph replay",
                    "refresh": "full (synchronous layer)", "schedule": args.schedule},

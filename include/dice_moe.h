@@ -78,14 +78,20 @@ typedef enum {
     MOE_REFRESH_ALG4 = 1,           /* Algorithm 4: slot 0 always; other slots iff step_t % stride_n == 0 */
     MOE_REFRESH_FRACTION_TOKEN = 2, /* the n_units tokens with the largest top-1 score, all their slots */
     MOE_REFRESH_FRACTION_PAIR = 3,  /* the first n_units pairs in the order (slot asc, score desc, token asc) */
-    MOE_REFRESH_NONE = 4            /* no pair: the output is rebuilt from the cache */
+    MOE_REFRESH_NONE = 4,           /* no pair: the output is rebuilt from the cache */
+    /* Ablation of which pair is deprioritised (Section 5.3, "Conditional Communication"; ablation
+     * table rows "High Score" and "Random"): Algorithm 4 with another always-fresh slot. */
+    MOE_REFRESH_ALG4_HIGH = 5,      /* slot k-1 (lowest activated score) always; others iff step_t % stride_n == 0 */
+    MOE_REFRESH_ALG4_RANDOM = 6     /* one slot per token always, slot = mix32(seed = n_units, token) mod k, where
+                                       mix32(s, i): h = s*0x9E3779B9 + i; h ^= h>>16; h *= 0x85EBCA6B; h ^= h>>13;
+                                       h *= 0xC2B2AE35; h ^= h>>16 (mod 2^32); others iff step_t % stride_n == 0 */
 } moe_policy_kind;
 
 typedef struct {
     int32_t kind;             /* moe_policy_kind */
     int32_t step_t, stride_n; /* ALG4: step_t >= 0, stride_n >= 1 */
     int32_t n_units;          /* FRACTION_TOKEN: 0..T tokens; FRACTION_PAIR: 0..T*k pairs.  The
-                                 caller rounds a fraction to this integer. */
+                                 caller rounds a fraction to this integer.  ALG4_RANDOM: the seed. */
     int32_t use_fresh_scores; /* which score scales a reused cached output (supplement, "Expert
                                  Score Scaling"): 0 = the cached score that belonged to the stale
                                  input (the paper's choice), 1 = this step's score */

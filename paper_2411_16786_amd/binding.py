@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libdicemoe.so")
 
 MOE_F32, MOE_BF16 = 0, 1
 REFRESH_ALL, REFRESH_ALG4, REFRESH_FRACTION_TOKEN, REFRESH_FRACTION_PAIR, REFRESH_NONE = range(5)
+REFRESH_ALG4_HIGH, REFRESH_ALG4_RANDOM = 5, 6      # ablation variants (n_units carries RANDOM's seed)
 
 MOE_OK = 0
 MOE_ERR_NULL, MOE_ERR_SHAPE, MOE_ERR_DTYPE, MOE_ERR_POLICY = -1, -2, -3, -4
@@ -116,7 +117,7 @@ class Policy:
             return T * k + shared
         if self.kind == REFRESH_NONE:
             return shared
-        if self.kind == REFRESH_ALG4:
+        if self.kind in (REFRESH_ALG4, REFRESH_ALG4_HIGH, REFRESH_ALG4_RANDOM):
             return (T * k if self.step_t % self.stride_n == 0 else T) + shared
         if self.kind == REFRESH_FRACTION_TOKEN:
             return min(max(self.n_units, 0), T) * k + shared

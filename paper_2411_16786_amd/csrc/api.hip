@@ -129,15 +129,17 @@ int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* ex
     switch (policy->kind) {
     case MOE_REFRESH_ALL:
     case MOE_REFRESH_NONE:
-        return hip_result(ctx, launch_refresh_simple(policy->kind, T, s.k, s.n_shared, 0, 1, mask, n_refresh, st),
+        return hip_result(ctx, launch_refresh_simple(policy->kind, T, s.k, s.n_shared, 0, 1, 0u, mask, n_refresh, st),
                           "moe_conditional_refresh");
     case MOE_REFRESH_ALG4:
+    case MOE_REFRESH_ALG4_HIGH:
+    case MOE_REFRESH_ALG4_RANDOM:
         if (policy->stride_n < 1 || policy->step_t < 0)
             return fail(ctx, MOE_ERR_POLICY, "ALG4 needs step_t >= 0 and stride_n >= 1 (got %ld, %ld)",
                         policy->step_t, policy->stride_n);
         return hip_result(ctx,
-                          launch_refresh_simple(MOE_REFRESH_ALG4, T, s.k, s.n_shared, policy->step_t, policy->stride_n, mask,
-                                                n_refresh, st),
+                          launch_refresh_simple(policy->kind, T, s.k, s.n_shared, policy->step_t, policy->stride_n,
+                                                static_cast<uint32_t>(policy->n_units), mask, n_refresh, st),
                           "moe_conditional_refresh");
     case MOE_REFRESH_FRACTION_TOKEN:
         if (policy->n_units < 0 || policy->n_units > T)
@@ -152,7 +154,7 @@ int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* ex
             return fail(ctx, MOE_ERR_POLICY, "FRACTION_PAIR n_units=%ld outside 0..T*k=%ld", policy->n_units, N);
         if (!scores) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: scores is null");
         if (policy->n_units == N)
-            return hip_result(ctx, launch_refresh_simple(MOE_REFRESH_ALL, T, s.k, s.n_shared, 0, 1, mask, n_refresh, st),
+            return hip_result(ctx, launch_refresh_simple(MOE_REFRESH_ALL, T, s.k, s.n_shared, 0, 1, 0u, mask, n_refresh, st),
                               "moe_conditional_refresh");
         // slots before `slot` are refreshed for every token, slot `slot` for its m best tokens
         const int slot = T > 0 ? policy->n_units / T : 0;

@@ -13,8 +13,8 @@ hipError_t launch_gate(bool bf16, const void* x, const void* Wg, const float* bg
 
 // kind: 0 all, 1 Algorithm 4, 4 none (elementwise policies).  mask has k + n_shared columns; the
 // shared slots are refreshed under every policy
-hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int step_t, int stride_n, uint8_t* mask,
-                                 int32_t* n_refresh, hipStream_t stream);
+hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int step_t, int stride_n, uint32_t seed,
+                                 uint8_t* mask, int32_t* n_refresh, hipStream_t stream);
 // exact top-m selection of tokens by scores[i*k + slot] (descending, ties to the lower token);
 // token_mode: selected tokens get all k slots; otherwise slots < slot are all refreshed, slot
 // `slot` follows the selection and later slots are not refreshed

@@ -11,9 +11,21 @@
 
 namespace dicemoe {
 
-// kc = columns of the mask (k routed slots, then the shared-expert slots, which are always refreshed)
+// Counter-based draw of the "Random" ablation variant: the 32-bit avalanche step of MurmurHash3 (a
+// published bit mixer) on seed * 0x9E3779B9 + token, modulo 2^32.
+__device__ __forceinline__ uint32_t mix32(uint32_t seed, uint32_t token) {
+    uint32_t h = seed * 0x9E3779B9u + token;
+    h ^= h >> 16; h *= 0x85EBCA6Bu;
+    h ^= h >> 13; h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+
+// kc = columns of the mask (k routed slots, then the shared-expert slots, which are always refreshed).
+// kind 1 / 5 / 6: Algorithm 4 with the always-fresh slot being the top-1 slot, the last activated
+// slot ("High Score" deprioritised) or a slot drawn per token ("Random"), Section 5.3 ablation.
 __global__ __launch_bounds__(256) void refresh_simple_kernel(int kind, int N, int kc, int k, int off_step,
-                                                             uint8_t* __restrict__ mask,
+                                                             uint32_t seed, uint8_t* __restrict__ mask,
                                                              int32_t* __restrict__ n_refresh, int n_value)
 {
     const int p = blockIdx.x * blockDim.x + threadIdx.x;
@@ -24,7 +36,12 @@ __global__ __launch_bounds__(256) void refresh_simple_kernel(int kind, int N, in
     if (j >= k) m = 1;                                      // shared expert: fresh in every step
     else if (kind == 0) m = 1;                              // every pair
     else if (kind == 4) m = 0;                              // no pair
-    else m = (j == 0 || !off_step) ? 1 : 0;                 // top-1 slot always, others on t mod n == 0
+    else {
+        int fresh_slot = 0;                                 // top-1 slot always, others on t mod n == 0
+        if (kind == 5) fresh_slot = k - 1;
+        else if (kind == 6) fresh_slot = static_cast<int>(mix32(seed, static_cast<uint32_t>(p / kc)) % static_cast<uint32_t>(k));
+        m = (j == fresh_slot || !off_step) ? 1 : 0;
+    }
     mask[p] = m;
 }
 
@@ -126,8 +143,8 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
     }
 }
 
-hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int step_t, int stride_n, uint8_t* mask,
-                                 int32_t* n_refresh, hipStream_t stream)
+hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int step_t, int stride_n, uint32_t seed,
+                                 uint8_t* mask, int32_t* n_refresh, hipStream_t stream)
 {
     const int kc = k + n_shared;
     const int N = T_tok * kc;
@@ -137,8 +154,8 @@ hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int s
     else { off_step = (step_t % stride_n) != 0; n_value = off_step ? T_tok : T_tok * k; }
     n_value += T_tok * n_shared;
     const int blocks = N > 0 ? (N + 255) / 256 : 1;
-    hipLaunchKernelGGL(refresh_simple_kernel, dim3(blocks), dim3(256), 0, stream, kind, N, kc, k, off_step, mask,
-                       n_refresh, n_value);
+    hipLaunchKernelGGL(refresh_simple_kernel, dim3(blocks), dim3(256), 0, stream, kind, N, kc, k, off_step, seed,
+                       mask, n_refresh, n_value);
     return hipGetLastError();
 }
 

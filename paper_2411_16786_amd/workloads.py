@@ -54,6 +54,10 @@ CONFIGS: Dict[int, MoEConfig] = {
                  notes="batch 8 x 1024 tokens, two consecutive diffusion steps"),
     5: MoEConfig(5, "ep-shard-zipf", "bf16", T=8192, d=2048, E=16, k=2, F=8192, ep_world=4,
                  notes="4 local experts of a 4-way expert-parallel layout, Zipf(1.2) load"),
+    # the paper's second model (Section 5.1): 16 experts x 40 layers.  The paper gives no widths;
+    # d = 1792 is the published DiT-MoE-G/2 hidden size, F = 4d as in the other workloads.
+    6: MoEConfig(6, "dit-moe-g", "bf16", T=4096, d=1792, E=16, k=2, F=7168, layers=40,
+                 notes="batch 16 x 256 tokens, router bias gives uneven load, 40 layers"),
 }
 
 
@@ -136,7 +140,7 @@ def make_layer(cfg: int, layer: int = 0, bump: int = 0, with_experts: bool = Tru
     x = to_storage(x, c.dtype)
     Wg = _normal(rng, (c.E, c.d), 1.0 / np.sqrt(c.d), c.dtype)
     bg = None
-    if cfg == 3:
+    if cfg in (3, 6):
         bg = (rng.standard_normal(c.E, dtype=np.float32) * np.float32(0.5)).astype(np.float32)
     elif cfg == 5:
         # router bias = log of the Zipf(1.2) weights: expert load follows the Zipf law

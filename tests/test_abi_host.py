@@ -135,7 +135,8 @@ def test_policy_row_count_matches_the_oracle_mask():
         s = rng.random((T, k))
         s = -np.sort(-s, axis=1)            # slot 0 carries the largest score, as the router emits them
         cases = [B.Policy(B.REFRESH_ALL), B.Policy(B.REFRESH_NONE)]
-        cases += [B.Policy(B.REFRESH_ALG4, step_t=t, stride_n=n) for n in (1, 2, 3) for t in range(4)]
+        cases += [B.Policy(kind, step_t=t, stride_n=n, n_units=5) for n in (1, 2, 3) for t in range(4)
+                  for kind in (B.REFRESH_ALG4, B.REFRESH_ALG4_HIGH, B.REFRESH_ALG4_RANDOM)]
         cases += [B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=u) for u in (0, 1, T // 2, T)]
         cases += [B.Policy(B.REFRESH_FRACTION_PAIR, n_units=u) for u in (0, 1, T, T * k // 2 + 1, T * k)]
         for pol in cases:

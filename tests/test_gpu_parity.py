@@ -108,6 +108,10 @@ def test_refresh_mask_bit_exact(T, k):
     for t in range(4):
         for n in (1, 2, 3):
             pols.append(B.Policy(B.REFRESH_ALG4, step_t=t, stride_n=n))
+            # ablation variants: lowest activated slot / a drawn slot stays fresh (n_units = seed)
+            pols.append(B.Policy(B.REFRESH_ALG4_HIGH, step_t=t, stride_n=n))
+            pols.append(B.Policy(B.REFRESH_ALG4_RANDOM, step_t=t, stride_n=n, n_units=1000 * n + t))
+    pols.append(B.Policy(B.REFRESH_ALG4_RANDOM, step_t=1, stride_n=2, n_units=-7))       # seed taken modulo 2^32
     for n_units in sorted({0, 1, T // 4, T // 3 + 17 if T > 100 else T // 2, T // 2, (3 * T) // 4, T - 1, T} - {-1}):
         if 0 <= n_units <= T:
             pols.append(B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=n_units))
@@ -430,6 +434,17 @@ def test_layer_config3_xl_full_size_sampled(layer):
     say(f"  expert load max/mean = {load.max():.2f}")
     assert 1.2 < load.max() < 4.0            # moderately uneven
     sampled_layer_check(g, st, li, 2, f"cfg3 layer {layer}", seed=layer)
+
+
+def test_layer_dit_moe_g_shape_full_size_sampled():
+    """The paper's second model shape (Section 5.1: 16 experts; 40 layers of it in the benchmark):
+    one full-size layer, integer stages in full, FFN rows and outputs on a sample."""
+    li, z = G.pick_layer(6)
+    say(f"DiT-MoE-G shape, seed {li.seed}")
+    g = G.GpuLayer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, 2, "bf16")
+    g.forward()
+    st = oracle_index_stages(li, 2, z)
+    sampled_layer_check(g, st, li, 2, "dit-moe-g", n_rows=48, n_tok=32, seed=6)
 
 
 # ----------------------------------------------------------------------------- shared experts
