@@ -294,6 +294,9 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
                                         int row_div = 1, const int32_t* out_index = nullptr)
 {
     constexpr int kComputeUnits = 256;
+    // tiles dealt to the XCDs by expert (one L2 per XCD: an expert's weight slabs are then fetched by one
+    // XCD) whenever the segment table fits the lanes of a wavefront; else bands of row tiles
+    const int by_expert = n_seg <= 64 ? 1 : 0;
     // expected tiles: every segment ends in a partial row tile, half a tile on average
     auto tiles = [&](int bm, int bn) {
         const long long m_tiles = (static_cast<long long>(max_rows) + static_cast<long long>(n_seg) * bm / 2 + bm - 1) / bm;
@@ -302,13 +305,13 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
     const bool fits_192 = (N + 191) / 192 * 192 * 8 <= N * 9;          // at most 1/8 of the columns computed in vain
     if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6) {
         if (K >= 256)
-            return launch_gemm_bf16_wide<4, 3, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index);
-        return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index);
+            return launch_gemm_bf16_wide<4, 3, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
+        return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
     }
     if (fits_192 && K >= 256 && tiles(128, 192) <= kComputeUnits && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index);
+        return launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
     if (fits_192 && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index);
+        return launch_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
     return launch_gemm_bf16<128, 128, 3, true, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
                                                            row_div, out_index);
 }

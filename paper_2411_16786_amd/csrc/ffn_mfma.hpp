@@ -80,6 +80,90 @@ __device__ __forceinline__ bool find_row_tile(const int32_t* __restrict__ seg_of
     return false;
 }
 
+// Tile of workgroup `block` when the tiles are dealt to the eight XCDs by expert.  Workgroups go to
+// the XCDs round robin (XCD = block mod 8) and every XCD has an L2 of its own, so the tiles that share
+// an expert's weights should run on one XCD: each XCD then reads about one eighth of the weights
+// instead of the slabs of every expert its share of a row-band ordering happens to touch.
+//   home XCD of segment g = seg_expert[g] mod 8; an XCD's own list = the tiles of its segments, in
+//   segment order, inside a segment in bands of `group_m` row tiles (row tile fastest);
+//   cap = ceil(total tiles / 8): an XCD keeps the first cap tiles of its list; what is beyond the
+//   cap (a hot expert) forms the overflow list, in XCD order, and is taken, in XCD order, by the
+//   XCDs whose own list is shorter than cap.  Every tile is assigned exactly once and no XCD gets
+//   more than cap; the grid must hold at least 8 * cap workgroups.
+__device__ __forceinline__ bool find_tile_by_expert(const int32_t* __restrict__ seg_offsets,
+                                                    const int32_t* __restrict__ seg_expert, int n_seg, int BM,
+                                                    int n_tiles_n, int group_m, int block, int& seg, int& row0,
+                                                    int& row_end, int& tile_n)
+{
+    // n_seg <= 64: lane g holds segment g (one vector load instead of a walk of dependent scalar loads);
+    // the uniform loops below pick the entries out with readlane
+    const int lane = threadIdx.x & 63;
+    int my_begin = 0, my_end = 0, my_home = 8;
+    if (lane < n_seg) {
+        my_begin = seg_offsets[lane];
+        my_end = seg_offsets[lane + 1];
+        my_home = seg_expert[lane] & 7;
+    }
+    const int my_nt = (my_end - my_begin + BM - 1) / BM;
+    const int x = block & 7, s = block >> 3;
+    int own[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) own[i] = 0;
+    for (int g = 0; g < n_seg; ++g) {
+        const int tiles = __builtin_amdgcn_readlane(my_nt, g) * n_tiles_n;
+        const int home = __builtin_amdgcn_readlane(my_home, g);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) own[i] += (home == i) ? tiles : 0;
+    }
+    int total = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) total += own[i];
+    if (total == 0) return false;
+    const int cap = (total + 7) >> 3;
+    int own_x = 0, spare_before = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int kept = own[i] < cap ? own[i] : cap;
+        if (i == x) own_x = own[i];
+        if (i < x) spare_before += cap - kept;
+    }
+    const int kept_x = own_x < cap ? own_x : cap;
+    int list = x, idx = s;
+    if (s >= kept_x) {                               // a slot beyond this XCD's own tiles takes overflow
+        const int o = s - kept_x;
+        if (o >= cap - kept_x) return false;
+        int pos = spare_before + o;
+        list = -1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int over = own[i] > cap ? own[i] - cap : 0;
+            if (list < 0) {
+                if (pos < over) { list = i; idx = cap + pos; }
+                else pos -= over;
+            }
+        }
+        if (list < 0) return false;
+    }
+    for (int g = 0; g < n_seg; ++g) {
+        if (__builtin_amdgcn_readlane(my_home, g) != list) continue;
+        const int nt = __builtin_amdgcn_readlane(my_nt, g);
+        const int tiles = nt * n_tiles_n;
+        if (idx < tiles) {
+            const int band = idx / (group_m * n_tiles_n), in_band = idx % (group_m * n_tiles_n);
+            const int left = nt - band * group_m;
+            const int rows_here = left < group_m ? left : group_m;
+            const int tile_m = band * group_m + in_band % rows_here;
+            tile_n = in_band / rows_here;
+            seg = g;
+            row0 = __builtin_amdgcn_readlane(my_begin, g) + tile_m * BM;
+            row_end = __builtin_amdgcn_readlane(my_end, g);
+            return true;
+        }
+        idx -= tiles;
+    }
+    return false;
+}
+
 // chunk swizzle for 128-byte rows (8 chunks): any 8 or 16 consecutive rows at one logical chunk fall
 // on distinct 16-byte bank groups.
 template <int CH> __device__ __forceinline__ int chunk_swizzle(int row);

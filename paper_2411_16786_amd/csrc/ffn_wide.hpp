@@ -25,26 +25,30 @@ __device__ __forceinline__ void wait_lgkmcnt() {
 #define DICEMOE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // workgroups per compute unit that the LDS footprint allows (the register budget follows from it)
-constexpr int wide_occupancy(int tm, int tn, int ast, int wst) { return (ast * tm + wst * tn) * 64 * 128 <= 80 * 1024 ? 2 : 1; }
+constexpr int wide_occupancy(int tm, int tn, int ast, int wst, int wgm, int wgn) {
+    return (ast * tm * wgm + wst * tn * wgn) * 32 * 128 <= 80 * 1024 ? 2 : 1;
+}
 
-template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG>
-__global__ __launch_bounds__(256, wide_occupancy(TM, TN, AST, WST)) void ffn_gemm_bf16_wide_kernel(
+template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WGM, WGN)) void ffn_gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
     const int32_t* __restrict__ seg_expert, int n_seg, int n_tiles_n, int m_tiles_max,
-    const int32_t* __restrict__ row_index, int row_div, const int32_t* __restrict__ out_index)
+    const int32_t* __restrict__ row_index, int row_div, const int32_t* __restrict__ out_index, int by_expert)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
+    constexpr int NW = WGM * WGN;                  // wavefronts, WGM along the rows by WGN along the columns
+    constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
     constexpr int WM = 32 * TM, WN = 32 * TN;
     constexpr int CH = 8;                          // 16-byte chunks per 64-deep tile row
-    constexpr int QA = BM / 32, QB = BN / 32;      // direct-to-LDS loads per wavefront and stage (8 rows each)
+    constexpr int QA = BM / (8 * NW), QB = BN / (8 * NW);      // direct-to-LDS loads per wavefront and stage (8 rows each)
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "every wavefront loads whole groups of eight rows");
     constexpr int QW = QA + QB;
     constexpr int ABYTES = BM * 128, WBYTES = BN * 128;      // one stage of each operand
     constexpr int NFRAG = TM + TN;
     constexpr int NMFMA = TM * TN;
     constexpr int GROUP_M = 8;
     constexpr int REGION = epilogue_region_bytes<TN>();
-    static_assert(4 * REGION <= AST * ABYTES + WST * WBYTES, "epilogue slabs must fit in the stage buffers");
+    static_assert(NW * REGION <= AST * ABYTES + WST * WBYTES, "epilogue slabs must fit in the stage buffers");
     static_assert((AST == 2 && (WST == 2 || WST == 3)) || (AST == 3 && WST == 3), "ring depths (A, W): (2,2), (2,3), (3,3)");
     static_assert(NMFMA >= NFRAG, "one fragment read per MFMA slot");
     static_assert(SPREAD >= 1 && SPREAD <= 4, "a refill is issued within the four slices before it is needed");
@@ -53,24 +57,34 @@ __global__ __launch_bounds__(256, wide_occupancy(TM, TN, AST, WST)) void ffn_gem
     char* const w_lds = smem + AST * ABYTES;
 
     // ---- which tile (bands of GROUP_M row tiles, XCD x takes the x-th eighth of the sequence)
-    const int t = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int band = t / (GROUP_M * n_tiles_n);
-    const int in_band = t % (GROUP_M * n_tiles_n);
-    const int left = m_tiles_max - band * GROUP_M;
-    const int rows_here = left < GROUP_M ? left : GROUP_M;
-    if (rows_here <= 0) return;
-    const int tile_m = band * GROUP_M + in_band % rows_here;
-    const int tile_n = in_band / rows_here;
-    if (tile_n >= n_tiles_n) return;
-    int seg, row0, row_end;
-    if (!find_row_tile(seg_offsets, n_seg, BM, tile_m, seg, row0, row_end)) return;
+    int seg, row0, row_end, tile_n;
+    if (by_expert) {
+        if (!find_tile_by_expert(seg_offsets, seg_expert, n_seg, BM, n_tiles_n, GROUP_M, blockIdx.x, seg, row0, row_end,
+                                 tile_n))
+            return;
+    } else {
+        const int t = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+        const int band = t / (GROUP_M * n_tiles_n);
+        const int in_band = t % (GROUP_M * n_tiles_n);
+        const int left = m_tiles_max - band * GROUP_M;
+        const int rows_here = left < GROUP_M ? left : GROUP_M;
+        if (rows_here <= 0) return;
+        const int tile_m = band * GROUP_M + in_band % rows_here;
+        tile_n = in_band / rows_here;
+        if (tile_n >= n_tiles_n) return;
+        if (!find_row_tile(seg_offsets, n_seg, BM, tile_m, seg, row0, row_end)) return;
+    }
+    if (DIAG & 8) {                                 // timing aid: the tile lookup alone
+        if (seg + row0 + row_end + tile_n == -12345) C[0] = 1;
+        return;
+    }
     const int e = seg_expert[seg];
     const int n0 = tile_n * BN;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
 
     // bias of this wavefront's columns, fetched now and used in the epilogue
     const int col_first = n0 + wn * WN;
@@ -325,14 +339,14 @@ __global__ __launch_bounds__(256, wide_occupancy(TM, TN, AST, WST)) void ffn_gem
                              out_index);
 }
 
-template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG = 0>
+template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG = 0, int WGM = 2, int WGN = 2>
 static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
-                                        int row_div = 1, const int32_t* out_index = nullptr)
+                                        int row_div = 1, const int32_t* out_index = nullptr, int by_expert = 0)
 {
-    constexpr int BM = 64 * TM, BN = 64 * TN;
-    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, AST, WST, GELU, DIAG>;
+    constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
+    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, AST, WST, GELU, DIAG, WGM, WGN>;
     constexpr int smem = (AST * BM + WST * BN) * 128;
     if (WST == 3 && K < 4 * 64) return hipErrorInvalidValue;      // the three-deep loops are written for at least four steps
     static bool configured = false;
@@ -345,9 +359,9 @@ static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const floa
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
     const int bands = (m_tiles + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n), dim3(256), smem, stream,
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n), dim3(64 * WGM * WGN), smem, stream,
                        static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, static_cast<bf16_t*>(C), N,
-                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index, row_div, out_index);
+                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index, row_div, out_index, by_expert);
     return hipGetLastError();
 }
 

@@ -232,22 +232,29 @@ WIDE_FFN_CASES = [
     ("k-192", [900, 411, 1200, 777], 192, 1536),
     ("k-256", [900, 411, 1200, 777], 256, 1536),
     ("k-256-few-rows", [90, 41, 300, 77], 256, 4608),                             # three stages at four steps
+    # tile-to-XCD dealing: one hot expert whose tiles spill over to the other XCDs' spare slots; many
+    # segments that share five experts (three XCDs own nothing); more segments than a wavefront has
+    # lanes (row-band order instead); sixteen experts, two per XCD
+    ("hot-expert", [5000, 100, 0, 100, 37, 100, 263, 2592], 384, 1536),
+    ("forty-segments-five-experts", [150 + 37 * (g % 7) for g in range(40)], 384, 1536, [g % 5 for g in range(40)]),
+    ("eighty-segments", [64 + 11 * (g % 9) for g in range(80)], 384, 1536, [g % 8 for g in range(80)]),
+    ("sixteen-experts", [512 + 90 * ((g * 5) % 7) - 200 * (g % 2) for g in range(16)], 384, 1536),
 ]
 
 
 @pytest.mark.parametrize("case", WIDE_FFN_CASES, ids=[c[0] for c in WIDE_FFN_CASES])
 def test_expert_ffn_wide_tiles_on_sampled_rows(case):
-    name, seg_rows, d, F = case
+    name, seg_rows, d, F = case[:4]
     say(f"wide ffn case {name}")
     dtype = "bf16"
-    E = len(seg_rows)
+    seg_expert = np.asarray(case[4], np.int32) if len(case) > 4 else np.roll(np.arange(len(seg_rows), dtype=np.int32), 3)
+    E = int(seg_expert.max()) + 1
     rows = int(sum(seg_rows))
     # weights of the order of 1/sqrt(fan-in), as in the workloads: outputs of order one, for which the
     # absolute bf16 tolerance is written
     _, _, _, W1, b1, W2, b2 = G.small_inputs(51, 4, d, E, F, dtype, bias=True, w_std=0.02)
     r = np.random.Generator(np.random.PCG64(52))
     xp = WL.to_storage(r.standard_normal((rows, d), dtype=np.float32), dtype)
-    seg_expert = np.roll(np.arange(E, dtype=np.int32), 3)
     seg_offsets = np.concatenate([[0], np.cumsum(seg_rows)]).astype(np.int32)
     ctx = B.Context(rows + 8, d, F, E, 1, dtype)
     h = torch.full((rows + 8, d), 9.0, dtype=ctx.torch_dtype, device=G.DEV)
@@ -259,7 +266,7 @@ def test_expert_ffn_wide_tiles_on_sampled_rows(case):
     torch.cuda.synchronize()
     h_gpu = G.to_np(h)
     edge = []
-    for g in range(E):
+    for g in range(len(seg_rows)):
         lo, hi = int(seg_offsets[g]), int(seg_offsets[g + 1])
         edge += [q for q in (lo, lo + 1, hi - 2, hi - 1) if lo <= q < hi]
     sel = np.unique(np.concatenate([np.array(edge, dtype=np.int64), r.integers(0, rows, 160)])).astype(np.int32)
