@@ -238,17 +238,30 @@ __device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* reg
         const int r = row_first + (lane + 64 * p) / CPR;
         dst_row[p] = r < row_end ? (out_index ? out_index[r] : r) : -1;
     }
-    // phase 1: arithmetic and parking, no LDS read in between (nothing to wait for)
+    // phase 1: arithmetic and parking, no LDS read in between (nothing to wait for).  A lane holds four
+    // consecutive columns per group (columns 8g + 4h .. + 3 of block j, h = lane / 32).  Two groups at a
+    // time, the two half-wavefronts swap one register pair (v_permlane32_swap) so that every lane ends up
+    // with eight consecutive columns: half the LDS writes, 16 bytes each, and the 16 lanes of a write
+    // cycle cover all banks (with 8-byte writes two rows shared their banks).
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int nl = j * 32 + 8 * g + 4 * h;
-            float v0 = half[j][4 * g] + bb[j][g].x, v1 = half[j][4 * g + 1] + bb[j][g].y;
-            float v2 = half[j][4 * g + 2] + bb[j][g].z, v3 = half[j][4 * g + 3] + bb[j][g].w;
-            if (GELU) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
-            uint2 packed = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
-            *reinterpret_cast<uint2*>(region + m_local * PITCH + nl * 2) = packed;
+        for (int gp = 0; gp < 2; ++gp) {
+            uint2 packed[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int g = 2 * gp + q;
+                float v0 = half[j][4 * g] + bb[j][g].x, v1 = half[j][4 * g + 1] + bb[j][g].y;
+                float v2 = half[j][4 * g + 2] + bb[j][g].z, v3 = half[j][4 * g + 3] + bb[j][g].w;
+                if (GELU) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
+                packed[q] = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+            }
+            // lanes 0..31 keep group 2gp and receive its upper four columns from lanes 32..63, which in turn
+            // receive group 2gp+1's lower four columns
+            const auto sx = __builtin_amdgcn_permlane32_swap(packed[0].x, packed[1].x, false, false);
+            const auto sy = __builtin_amdgcn_permlane32_swap(packed[0].y, packed[1].y, false, false);
+            const int nl = j * 32 + 16 * gp + 8 * h;
+            *reinterpret_cast<u32x4_v*>(region + m_local * PITCH + nl * 2) = u32x4_v{sx[0], sy[0], sx[1], sy[1]};
         }
     __builtin_amdgcn_wave_barrier();
     // phase 2: all row-contiguous pieces of the slab in one batch of LDS reads, then the stores
