@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--workload", choices=["xl", "g"], default="xl",
                     help="xl: DiT-MoE-XL shape x 28 layers (the headline workload); g: DiT-MoE-G shape (16 experts, "
                          "d=1792) x 40 layers")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="tokens per layer call instead of the workload's (smaller local batches; not the headline)")
     ap.add_argument("--eager", action="store_true", help="launch from Python every step instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -66,7 +68,7 @@ def main():
     wl_cfg = 3 if args.workload == "xl" else 6
     c = WL.CONFIGS[wl_cfg]
     n_layers = args.layers or c.layers
-    T, d, E, k, F = c.T, c.d, c.E, c.k, c.F
+    T, d, E, k, F = (args.tokens or c.T), c.d, c.E, c.k, c.F
     n_shared = args.n_shared
     N = T * (k + n_shared)          # (token, slot) pairs: k routed slots and one per shared expert
 
@@ -80,7 +82,7 @@ def main():
     cpu_layers = []
     with ThreadPoolExecutor(max_workers=8) as pool:
         for first in range(0, n_layers, 8):        # generated and uploaded eight layers at a time (host memory)
-            chunk = list(pool.map(lambda l: WL.make_layer(wl_cfg, layer=l, n_shared=n_shared),
+            chunk = list(pool.map(lambda l: WL.make_layer(wl_cfg, layer=l, n_shared=n_shared, T=T),
                                   range(first, min(first + 8, n_layers))))
             for li in chunk:
                 buf = B.LayerBuffers(ctx, dev, workspace=workspace)

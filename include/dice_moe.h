@@ -104,8 +104,9 @@ int moe_create(moe_ctx** out, const moe_shape* shape);
 int moe_destroy(moe_ctx* ctx);
 
 /* Bytes of device workspace that moe_conditional_refresh, moe_dispatch and moe_expert_ffn may
- * use for T_max tokens (the FFN's hidden activations [T_max*k, F] dominate).  One workspace can
- * serve all three calls of a layer, and all layers, on one stream. */
+ * use for T_max tokens: the FFN's hidden activations [T_max*k, F], and (MOE_BF16) 28 MB of float
+ * partial sums for the second GEMM when its reduction is split over several workgroups (few
+ * rows).  One workspace can serve all three calls of a layer, and all layers, on one stream. */
 size_t moe_workspace_bytes(const moe_ctx* ctx);
 
 /* Text of the last error recorded on this context ("" if none); valid until the next call. */

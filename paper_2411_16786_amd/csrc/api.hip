@@ -35,6 +35,12 @@ bool is_bf16(const moe_ctx* ctx) { return ctx->shape.dtype == MOE_BF16; }
 int slots(const moe_ctx* ctx) { return ctx->shape.k + ctx->shape.n_shared; }
 int experts(const moe_ctx* ctx) { return ctx->shape.E + ctx->shape.n_shared; }
 size_t elem_bytes(const moe_ctx* ctx) { return is_bf16(ctx) ? 2 : 4; }
+// workspace: [hidden activations of the FFN, rows x F][float partial sums of a split second GEMM (bf16 only)]
+size_t hidden_bytes(const moe_ctx* ctx)
+{
+    const size_t rows = static_cast<size_t>(ctx->shape.T_max) * slots(ctx);
+    return ((rows * ctx->shape.F * elem_bytes(ctx) + 255) / 256) * 256;
+}
 
 int check_T(moe_ctx* ctx, int32_t T)
 {
@@ -78,9 +84,7 @@ int moe_destroy(moe_ctx* ctx)
 size_t moe_workspace_bytes(const moe_ctx* ctx)
 {
     if (!ctx) return 0;
-    const size_t rows = static_cast<size_t>(ctx->shape.T_max) * slots(ctx);
-    const size_t hidden = rows * ctx->shape.F * (ctx->shape.dtype == MOE_BF16 ? 2 : 4);
-    return ((hidden + 255) / 256) * 256 + 4096;
+    return hidden_bytes(ctx) + (is_bf16(ctx) ? dicemoe::kSplitKBytes : 0) + 4096;
 }
 
 const char* moe_last_error(const moe_ctx* ctx) { return ctx ? ctx->err : "null context"; }
@@ -207,7 +211,8 @@ static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, 
     return hip_result(ctx,
                       launch_expert_ffn(is_bf16(ctx), x_rows, row_pairs, slots(ctx), seg_offsets, seg_expert, n_segments,
                                         max_rows, s.d, s.F, W1, b1, W2, b2, h_packed, out_pairs, workspace,
-                                        static_cast<hipStream_t>(stream)),
+                                        is_bf16(ctx) ? static_cast<char*>(workspace) + hidden_bytes(ctx) : nullptr,
+                                        is_bf16(ctx) ? dicemoe::kSplitKBytes : 0, static_cast<hipStream_t>(stream)),
                       who);
 }
 

@@ -242,6 +242,55 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
     }
 }
 
+// Second pass of a split reduction: C[r] = bf16(bias + partial[0][r] + partial[1][r] + ...), shares added in
+// index order (no atomics: the same bits in every run).  One workgroup per 16 rows of a segment.
+constexpr int kReduceRows = 16;
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int k_splits,
+                                                           int partial_rows, const float* __restrict__ bias,
+                                                           bf16_t* __restrict__ C, int N,
+                                                           const int32_t* __restrict__ seg_offsets,
+                                                           const int32_t* __restrict__ seg_expert, int n_seg,
+                                                           const int32_t* __restrict__ out_index)
+{
+    int seg, row0, row_end;
+    if (!find_row_tile(seg_offsets, n_seg, kReduceRows, blockIdx.x, seg, row0, row_end)) return;
+    const int e = seg_expert[seg];
+    const int groups = N / 8;                                   // 8 columns = 16 bytes of output per thread and turn
+    const int rows = (row_end - row0) < kReduceRows ? (row_end - row0) : kReduceRows;
+    const size_t share = static_cast<size_t>(partial_rows) * N;
+    for (int c = threadIdx.x; c < rows * groups; c += blockDim.x) {
+        const int r = row0 + c / groups;
+        const int n = (c % groups) * 8;
+        float v[8];
+        if (bias) {
+            const f32x4_v b0 = *reinterpret_cast<const f32x4_v*>(bias + static_cast<size_t>(e) * N + n);
+            const f32x4_v b1 = *reinterpret_cast<const f32x4_v*>(bias + static_cast<size_t>(e) * N + n + 4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { v[t] = b0[t]; v[4 + t] = b1[t]; }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = 0.f;
+        }
+        // the sum of the shares first, the bias last: the order of the unsplit kernel's epilogue
+        float acc[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = 0.f;
+        for (int sidx = 0; sidx < k_splits; ++sidx) {
+            const float* p = partial + sidx * share + static_cast<size_t>(r) * N + n;
+            const f32x4_v a0 = *reinterpret_cast<const f32x4_v*>(p);
+            const f32x4_v a1 = *reinterpret_cast<const f32x4_v*>(p + 4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { acc[t] += a0[t]; acc[4 + t] += a1[t]; }
+        }
+        const int dst = out_index ? out_index[r] : r;
+        if (dst < 0) continue;
+        u32x4_v packed;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) packed[t] = pack_bf16x2(acc[2 * t] + v[2 * t], acc[2 * t + 1] + v[2 * t + 1]);
+        *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(dst) * N + n) = packed;
+    }
+}
+
 template <int BM, int BN, int OCC, bool XCD, bool GELU>
 static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                    const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
@@ -291,7 +340,8 @@ template <bool GELU>
 static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
-                                        int row_div = 1, const int32_t* out_index = nullptr)
+                                        int row_div = 1, const int32_t* out_index = nullptr, float* partial = nullptr,
+                                        size_t partial_bytes = 0)
 {
     constexpr int kComputeUnits = 256;
     // tiles dealt to the XCDs by expert (one L2 per XCD: an expert's weight slabs are then fetched by one
@@ -303,6 +353,28 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
         return m_tiles * ((N + bn - 1) / bn);
     };
     const bool fits_192 = (N + 191) / 192 * 192 * 8 <= N * 9;          // at most 1/8 of the columns computed in vain
+    // Few rows and a long reduction (the second GEMM after a small refresh fraction or for a small batch):
+    // the 128 x 192 tiles do not fill the chip and each walks all of K.  With two or three workgroups per
+    // tile, each on a share of K (float partial sums in the workspace, added by a second pass in a fixed
+    // order), more compute units stream the weights at once: 54 -> 47 us at 2048 rows of the DiT-MoE-XL
+    // widths.  Not worth it once the tiles fill the chip by themselves (57 vs 66 us at 4096 rows).
+    if (!GELU && partial && fits_192 && by_expert) {
+        const long long t23 = tiles(128, 192);
+        int splits = 1;
+        if (t23 * 3 * 20 <= kComputeUnits * 21) splits = 3;
+        else if (t23 * 2 * 20 <= kComputeUnits * 21) splits = 2;
+        if (splits > 1 && K / 64 / splits >= 8 &&
+            static_cast<size_t>(splits) * max_rows * N * sizeof(float) <= partial_bytes) {
+            hipError_t err = launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, nullptr, C, N, K, seg_offsets, seg_expert, n_seg,
+                                                                       max_rows, stream, row_index, row_div, nullptr,
+                                                                       by_expert, partial, splits);
+            if (err != hipSuccess) return err;
+            const int blocks = (max_rows + kReduceRows - 1) / kReduceRows + n_seg;
+            hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, partial, splits, max_rows, bias,
+                               static_cast<bf16_t*>(C), N, seg_offsets, seg_expert, n_seg, out_index);
+            return hipGetLastError();
+        }
+    }
     if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6) {
         if (K >= 256)
             return launch_gemm_bf16_wide<4, 3, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
@@ -319,7 +391,8 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
 hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_index, int row_div,
                              const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
                              int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_packed,
-                             const int32_t* out_index, void* hidden, hipStream_t stream)
+                             const int32_t* out_index, void* hidden, void* partial, size_t partial_bytes,
+                             hipStream_t stream)
 {
     if (max_rows == 0) return hipSuccess;
     hipError_t err;
@@ -328,7 +401,7 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_i
                                           row_index, row_div);
         if (err != hipSuccess) return err;
         return launch_gemm_bf16_auto<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream,
-                                            nullptr, 1, out_index);
+                                            nullptr, 1, out_index, static_cast<float*>(partial), partial_bytes);
     }
     err = launch_gemm_f32<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
                                 row_div);

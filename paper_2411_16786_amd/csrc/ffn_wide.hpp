@@ -34,7 +34,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
     const int32_t* __restrict__ seg_expert, int n_seg, int n_tiles_n, int m_tiles_max,
-    const int32_t* __restrict__ row_index, int row_div, const int32_t* __restrict__ out_index, int by_expert)
+    const int32_t* __restrict__ row_index, int row_div, const int32_t* __restrict__ out_index, int by_expert,
+    float* __restrict__ partial, int partial_rows)
 {
     constexpr int NW = WGM * WGN;                  // wavefronts, WGM along the rows by WGN along the columns
     constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
@@ -49,7 +50,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     constexpr int GROUP_M = 8;
     constexpr int REGION = epilogue_region_bytes<TN>();
     static_assert(NW * REGION <= AST * ABYTES + WST * WBYTES, "epilogue slabs must fit in the stage buffers");
-    static_assert((AST == 2 && (WST == 2 || WST == 3)) || (AST == 3 && WST == 3), "ring depths (A, W): (2,2), (2,3), (3,3)");
+    static_assert((AST == 2 && (WST == 2 || WST == 3)) || (AST == 3 && WST == 3) || (AST == 4 && WST == 4),
+                  "ring depths (A, W): (2,2), (2,3), (3,3), (4,4)");
     static_assert(NMFMA >= NFRAG, "one fragment read per MFMA slot");
     static_assert(SPREAD >= 1 && SPREAD <= 4, "a refill is issued within the four slices before it is needed");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -166,7 +168,14 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[set][TM + j], fr[set][i], acc[i][j], 0, 0, 0);
     };
 
-    const int nk = K / 64;                          // the launcher guarantees nk >= 4 for a three-deep ring
+    // Split reduction: workgroup row blockIdx.y of the grid takes the y-th share of the 64-deep steps and
+    // leaves its float sums in partial[y] (a later pass adds the shares in a fixed order).  The launcher
+    // guarantees that every share has the steps the ring needs (>= 4 for a three-deep ring).
+    const int nk_all = K / 64;
+    const int k_begin = static_cast<int>(blockIdx.y) * nk_all / static_cast<int>(gridDim.y);
+    const int nk = (static_cast<int>(blockIdx.y) + 1) * nk_all / static_cast<int>(gridDim.y) - k_begin;
+    a_base += static_cast<size_t>(k_begin) * 128;
+    w_base += static_cast<size_t>(k_begin) * 128;
     // ---- prologue: every stage in flight, first fragments in registers.  The W parts go first: they
     // do not depend on the row index, whose load is still in flight when a gathering kernel gets here.
 #pragma unroll
@@ -301,6 +310,23 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
         step(kt, sa, sw, yes, pw, yes, no, yes, yes); advance(); ++kt;      // kt = nk-3: A(nk-1) is the last refill
         step(kt, sa, sw, yes, p0, no, no, yes, no); advance(); ++kt;        // kt = nk-2
         step(kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
+    } else if (AST == 4 && WST == 4) {
+        // three stages in flight per operand.  Loads younger than stage kt+1 at the barrier of step kt:
+        // step 0: A2, A3 of the prologue; step 1: A3 and refill 0; later: the last two refills
+        const std::integral_constant<int, 2 * QA> p2a{};
+        const std::integral_constant<int, QA + QW> paq{};
+        const std::integral_constant<int, 2 * QW> p2q{};
+        const std::integral_constant<int, QW> pq{};
+        step(0, 0, 0, yes, p2a, yes, yes, no, no);
+        advance();
+        step(1, sa, sw, yes, paq, yes, yes, yes, yes);
+        advance();
+        int kt = 2;
+        for (; kt + 4 < nk; ++kt) { step(kt, sa, sw, yes, p2q, yes, yes, yes, yes); advance(); }
+        step(kt, sa, sw, yes, p2q, no, no, yes, yes); advance(); ++kt;      // kt = nk-4: the last refill was issued at nk-5
+        step(kt, sa, sw, yes, pq, no, no, no, no); advance(); ++kt;         // kt = nk-3
+        step(kt, sa, sw, yes, p0, no, no, no, no); advance(); ++kt;         // kt = nk-2
+        step(kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
     } else {
         const std::integral_constant<int, QA> pa{};      // step 0: the prologue issued the A parts last
         const std::integral_constant<int, QW> pq{};      // the previous step's whole refill
@@ -328,6 +354,26 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
         if (s == 1234.5f) C[0] = 1;
         return;
     }
+    if (partial) {
+        // raw sums of this share: lane (m, h) holds, per 32 x 32 block, columns 8g + 4h .. + 3 of row m
+        float* dst = partial + static_cast<size_t>(blockIdx.y) * partial_rows * N;
+        const int m_local = lane & 31, h = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int r = row0 + wm * WM + i * 32 + m_local;
+            if (r >= row_end) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = col_first + j * 32 + 8 * g + 4 * h;
+                    if (n < N)
+                        *reinterpret_cast<f32x4_v*>(dst + static_cast<size_t>(r) * N + n) =
+                            f32x4_v{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                }
+        }
+        return;
+    }
     char* region = smem + wave * REGION;
     float* bias_lds = reinterpret_cast<float*>(region + slab_bytes<TN>());
     stage_bias<WN>(bias_reg, bias_lds, lane);
@@ -343,12 +389,17 @@ template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG = 0,
 static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
-                                        int row_div = 1, const int32_t* out_index = nullptr, int by_expert = 0)
+                                        int row_div = 1, const int32_t* out_index = nullptr, int by_expert = 0,
+                                        float* partial = nullptr, int k_splits = 1)
 {
     constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
     auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, AST, WST, GELU, DIAG, WGM, WGN>;
     constexpr int smem = (AST * BM + WST * BN) * 128;
-    if (WST == 3 && K < 4 * 64) return hipErrorInvalidValue;      // the three-deep loops are written for at least four steps
+    if (k_splits < 1 || (k_splits > 1 && (!partial || GELU))) return hipErrorInvalidValue;
+    const int nk_min = K / 64 / k_splits;                         // steps of the smallest share
+    if (WST == 3 && nk_min < 4) return hipErrorInvalidValue;      // the three-deep loops are written for at least four steps
+    if (WST == 4 && nk_min < 7) return hipErrorInvalidValue;      // the four-deep loop for at least seven
+    if (nk_min < 1) return hipErrorInvalidValue;
     static bool configured = false;
     if (!configured) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -359,9 +410,11 @@ static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const floa
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
     const int bands = (m_tiles + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n), dim3(64 * WGM * WGN), smem, stream,
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n, static_cast<unsigned>(k_splits)),
+                       dim3(64 * WGM * WGN), smem, stream,
                        static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, static_cast<bf16_t*>(C), N,
-                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index, row_div, out_index, by_expert);
+                       K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index, row_div, out_index, by_expert,
+                       k_splits > 1 ? partial : nullptr, max_rows);
     return hipGetLastError();
 }
 

@@ -37,7 +37,12 @@ hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, c
 hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_index, int row_div,
                              const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
                              int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_out,
-                             const int32_t* out_index, void* hidden, hipStream_t stream);
+                             const int32_t* out_index, void* hidden, void* partial, size_t partial_bytes,
+                             hipStream_t stream);
+
+// bytes of float partial sums that the split reduction of the second GEMM may use (beyond `hidden`)
+// (at most about 270 workgroups of 128 x 192 float tiles)
+constexpr size_t kSplitKBytes = static_cast<size_t>(288) * 128 * 192 * sizeof(float);
 
 // S_buffer[p] = scores[p] for the routed slots (j < k_cached) of every pair with mask[p] != 0 (all if mask is null)
 hipError_t launch_commit_scores(const float* scores, const uint8_t* mask, int T_tok, int k, int k_cached,

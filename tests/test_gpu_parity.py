@@ -224,7 +224,8 @@ WIDE_FFN_CASES = [
     # (name, rows per segment, d, F)
     ("xl-8192-rows", [1391, 612, 1204, 893, 1347, 701, 1120, 924], 1152, 4608),   # 128x192 x2 / 256x192
     ("xl-4096-rows", [695, 306, 602, 446, 673, 350, 560, 464], 1152, 4608),       # 128x192 x2 / three stages
-    ("xl-700-rows", [3, 250, 0, 129, 64, 1, 192, 61], 1152, 4608),                # three stages / 128x128
+    ("xl-2048-rows", [300, 200, 310, 250, 280, 190, 270, 248], 1152, 4608),       # second GEMM: K split in two
+    ("xl-700-rows", [3, 250, 0, 129, 64, 1, 192, 61], 1152, 4608),                # second GEMM: K split in three
     ("column-tails", [700, 0, 1033, 515, 390, 462], 1088, 1600),                  # widths not multiples of 192
     # short reductions in the first GEMM: one, two, three and four 64-deep steps (pipeline prologue / tail paths)
     ("k-64", [900, 411, 1200, 777], 64, 1536),
