@@ -243,8 +243,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
 }
 
 // Second pass of a split reduction: C[r] = bf16(bias + partial[0][r] + partial[1][r] + ...), shares added in
-// index order (no atomics: the same bits in every run).  One workgroup per 16 rows of a segment.
-constexpr int kReduceRows = 16;
+// index order (no atomics: the same bits in every run).  One workgroup per 4 rows of a segment.
+constexpr int kReduceRows = 4;
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int k_splits,
                                                            int partial_rows, const float* __restrict__ bias,
                                                            bf16_t* __restrict__ C, int N,
