@@ -324,8 +324,10 @@ static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bia
 
 // Tile shape for one bf16 grouped GEMM.  The wide kernel fetches fewer bytes per flop and keeps the
 // matrix pipe fed from hand-scheduled wavefronts, and wins as soon as its tiles fill most of the chip:
-//   256 x 192, one workgroup per compute unit, two stages of activations and three of weights (136 KB
-//     of LDS): the GEMM with the plain epilogue, when that grid covers most of the 256 compute units.
+//   256 x 192, one workgroup of eight wavefronts (4 x 2, each a 64 x 96 block; two per SIMD cover each
+//     other's waits, +1 % over four wavefronts of 128 x 96) per compute unit, two stages of activations
+//     and three of weights (136 KB of LDS): the GEMM with the plain epilogue, when that grid covers most
+//     of the 256 compute units.
 //     The weights stream from HBM exactly once; with a third stage each weight load has two steps of
 //     flight and the cold-weight penalty disappears (102 -> 88 us for GEMM2 at the DiT-MoE-XL shape);
 //   128 x 192, two stages (80 KB of LDS), two workgroups per compute unit: the GEMM whose epilogue
@@ -377,7 +379,7 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
     }
     if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6) {
         if (K >= 256)
-            return launch_gemm_bf16_wide<4, 3, 3, 2, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
+            return launch_gemm_bf16_wide<2, 3, 2, 2, 3, GELU, 0, 4, 2>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
         return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
     }
     if (fits_192 && K >= 256 && tiles(128, 192) <= kComputeUnits && tiles(128, 192) * 2 >= kComputeUnits)
