@@ -41,10 +41,12 @@ def main():
     ap.add_argument("--n-shared", type=int, default=0,
                     help="add this many shared experts (always-fresh dense FFNs; DiT-MoE carries 2) to every layer; "
                          "the headline workload has none")
-    ap.add_argument("--schedule", choices=["sync", "interweaved", "displaced"], default="sync",
+    ap.add_argument("--schedule", choices=["sync", "interweaved", "displaced", "dice"], default="sync",
                     help="step-level schedule of every layer (Algorithms 1-3); the headline workload is the synchronous "
                          "layer.  The asynchronous ones read the persistent combine buffer and run the expert call "
-                         "whose results the next step collects on a second stream")
+                         "whose results the next step collects on a second stream.  dice = the paper's combination: interweaved "
+                         "in the shallow half of the layers, synchronous in the deep half (Selective Synchronization), "
+                         "Algorithm 4 with stride 2 in every layer (Conditional Communication); launched eagerly")
     ap.add_argument("--workload", choices=["xl", "g"], default="xl",
                     help="xl: DiT-MoE-XL shape x 28 layers (the headline workload); g: DiT-MoE-G shape (16 experts, "
                          "d=1792) x 40 layers")
@@ -95,6 +97,7 @@ def main():
     setup_s = time.time() - t_setup
 
     deferred = None
+    step_no = [0]
     if args.schedule != "sync":
         from paper_2411_16786_amd import schedule as SCH
         deferred = torch.cuda.Stream()
@@ -112,9 +115,17 @@ def main():
                 B.moe_layer_forward(ctx, L["buf"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None,
                                     fuse_gather=not args.packed_dispatch)
             return
-        for L in layers:
-            SCH.moe_layer_step(args.schedule, L["state"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None,
-                               side_stream=deferred)
+        if args.schedule == "dice":
+            step_no[0] += 1
+            pol = B.Policy(B.REFRESH_ALG4, step_t=step_no[0], stride_n=2)
+            for i, L in enumerate(layers):
+                sched = SCH.INTERWEAVED if 2 * i < len(layers) else SCH.SYNC
+                SCH.moe_layer_step(sched, L["state"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None, policy=pol,
+                                   side_stream=deferred if sched != SCH.SYNC else None)
+        else:
+            for L in layers:
+                SCH.moe_layer_step(args.schedule, L["state"], L["x"], L["Wg"], L["bg"], L["W1"], None, L["W2"], None,
+                                   side_stream=deferred)
         torch.cuda.current_stream().wait_stream(deferred)      # the step ends when its deferred expert calls have
         for L in layers:
             L["state"].commit_done = None
@@ -125,7 +136,7 @@ def main():
     one_step()
     torch.cuda.synchronize()
     # (displaced alternates between two sets of layer buffers from step to step: launched eagerly)
-    if not args.eager and args.schedule != "displaced":
+    if not args.eager and args.schedule not in ("displaced", "dice"):
         graph = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -289,7 +300,9 @@ def main():
                                 f"DiT-MoE-G-shaped layer x {c.layers} (T={T}, d={d}, E={E}, top-{k}, F={F})")
                                + (f" + {n_shared} shared experts per layer" if n_shared else ""),
                    "layers": n_layers, "tokens": T, "launch": "eager" if graph is None else "hipGraph replay",
-                   "refresh": "full (synchronous layer)", "schedule": args.schedule},
+                   "refresh": ("full (synchronous layer)" if args.schedule != "dice" else
+                               "Algorithm 4, stride 2: every second step transmits the top-1 pairs only"),
+                   "schedule": args.schedule},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "stages": stages,
