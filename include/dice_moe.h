@@ -11,6 +11,10 @@
  *     x   <- scale(x_c, s)             moe_combine       (y_i = sum_e s_i^e h_i^e, Section 4.3)
  * and the per-pair transmit/reuse decision of Conditional Communication (supplement,
  * Algorithm 4) sits between router and dispatch:      moe_conditional_refresh.
+ * moe_expert_ffn_rows is moe_expert_ffn with the dispatch gather folded in; moe_expert_ffn_commit
+ * is the expert call of the asynchronous schedules (supplement, Algorithms 2 and 3), whose results
+ * go into the persistent combine buffer for the next step; moe_ep_segments describes an
+ * expert-parallel receive buffer to moe_expert_ffn.
  *
  * Conventions for every entry point
  *   - Returns MOE_OK (0) or a negative moe_status.  Never throws, aborts, allocates device
@@ -29,7 +33,7 @@
  *     Scores, probabilities, logits and biases are always float; indices are int32.
  *   - Weights are stored like a linear layer's weight, rows = output features:
  *       Wg[E][d],  W1[E][F][d],  b1[E][F],  W2[E][d][F],  b2[E][d].
- *   - Limits: 1 <= k <= E <= 64; d % 16 == 0 and F % 16 == 0; for MOE_BF16 also d % 64 == 0 and
+ *   - Limits: 1 <= k <= E, E + n_shared <= 64; d % 16 == 0 and F % 16 == 0; for MOE_BF16 also d % 64 == 0 and
  *     F % 64 == 0 (MFMA tile depth); T*k < 2^31 / max(d, F).
  */
 #ifndef DICE_MOE_H
