@@ -455,6 +455,19 @@ def test_layer_dit_moe_g_shape_full_size_sampled():
     sampled_layer_check(g, st, li, 2, "dit-moe-g", n_rows=48, n_tok=32, seed=6)
 
 
+@pytest.mark.parametrize("T", [4096, 1024, 300])
+def test_layer_is_bit_reproducible_at_the_xl_widths(T):
+    """No floating-point atomics anywhere and every reduction in a fixed order (the split second GEMM
+    included): two runs of the layer give the same bits, also when other work ran in between."""
+    li, _ = G.pick_layer(3, T=T)
+    g = G.GpuLayer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, 2, "bf16")
+    y1 = g.forward(fuse_gather=True).clone()
+    h1 = g.buf.h_packed.clone()
+    g.buf.h_packed.fill_(0); g.buf.y.fill_(0); g.buf.workspace.fill_(7)
+    y2 = g.forward(fuse_gather=True)
+    assert torch.equal(y1, y2) and torch.equal(h1, g.buf.h_packed)
+
+
 # ----------------------------------------------------------------------------- shared experts
 def shared_reference_tables(ref, E, n_shared):
     """Per-pair arrays of a layer with shared experts, from the oracle's routed result: the shared
