@@ -261,6 +261,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     for (int c = threadIdx.x; c < rows * groups; c += blockDim.x) {
         const int r = row0 + c / groups;
         const int n = (c % groups) * 8;
+        if (r >= partial_rows) continue;
         float v[8];
         if (bias) {
             const f32x4_v b0 = *reinterpret_cast<const f32x4_v*>(bias + static_cast<size_t>(e) * N + n);
@@ -363,10 +364,11 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
     if (!GELU && partial && fits_192 && by_expert) {
         const long long t23 = tiles(128, 192);
         int splits = 1;
-        if (t23 * 3 * 20 <= kComputeUnits * 21) splits = 3;
-        else if (t23 * 2 * 20 <= kComputeUnits * 21) splits = 2;
-        if (splits > 1 && K / 64 / splits >= 8 &&
-            static_cast<size_t>(splits) * max_rows * N * sizeof(float) <= partial_bytes) {
+        for (int sp = 3; sp >= 2 && splits == 1; --sp)       // the deepest split whose shares still fill the chip at most once
+            if (t23 * sp * 20 <= kComputeUnits * 21 && K / 64 / sp >= 8 &&
+                static_cast<size_t>(sp) * max_rows * N * sizeof(float) <= partial_bytes)
+                splits = sp;
+        if (splits > 1) {
             hipError_t err = launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, nullptr, C, N, K, seg_offsets, seg_expert, n_seg,
                                                                        max_rows, stream, row_index, row_div, nullptr,
                                                                        by_expert, partial, splits);

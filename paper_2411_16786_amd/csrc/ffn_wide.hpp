@@ -361,7 +361,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int r = row0 + wm * WM + i * 32 + m_local;
-            if (r >= row_end) continue;
+            if (r >= row_end || r >= partial_rows) continue;      // (the second: a caller whose max_rows is too small)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll

@@ -89,7 +89,8 @@ def moe_layer_step(schedule: str, st: LayerState, x, Wg, bg, W1, b1, W2, b2, pol
                      buf.workspace)
     if ns > 0:
         # shared experts: this step's x, within the step (they are replicated, never stale)
-        ctx.moe_expert_ffn_rows(x, buf.perm, buf.offsets[E:], buf.seg_expert[E:], T * ns, W1, b1, W2, b2,
+        # (max_rows bounds the packed row ids of the segments, which follow the routed rows)
+        ctx.moe_expert_ffn_rows(x, buf.perm, buf.offsets[E:], buf.seg_expert[E:], rows_routed + T * ns, W1, b1, W2, b2,
                                 buf.h_packed, buf.workspace)
     # x_c <- wait(h_c^prev); x <- scale(x_c, s): the routed slots come from the persistent buffer
     ctx.moe_combine(buf.h_packed, buf.inv, buf.scores[:T], st.mask_stale[:T], st.H, st.S,

@@ -86,6 +86,8 @@ CASES = [
     ("interweaved-bf16-shared", "bf16", 3, 300, 128, 8, 256, 2, 2, S.INTERWEAVED, "alg4", ()),
     ("interweaved-selective-sync", "bf16", 4, 256, 128, 8, 256, 2, 0, S.INTERWEAVED, "all", (2, 3)),
     ("interweaved-fresh-scores", "bf16", 2, 256, 128, 8, 256, 2, 0, S.INTERWEAVED, "alg4-fresh-scores", ()),
+    # expert width 1024: the second GEMM splits its reduction, with the scatter and with shared experts' segments
+    ("interweaved-split-k-shared", "bf16", 2, 256, 192, 4, 1024, 2, 1, S.INTERWEAVED, "alg4", ()),
     ("displaced-f32", "f32", 2, 96, 64, 4, 128, 2, 0, S.DISPLACED, "all", ()),
     ("displaced-bf16-alg4", "bf16", 3, 512, 128, 8, 256, 2, 0, S.DISPLACED, "alg4", ()),
     ("displaced-bf16-shared", "bf16", 2, 300, 128, 8, 256, 2, 1, S.DISPLACED, "alg4", (1,)),
