@@ -115,6 +115,29 @@ def test_interweaved_with_algorithm_4_mixes_one_step_and_older_entries():
     np.testing.assert_allclose(ys[3], r[2].y, rtol=1e-13, atol=1e-15)
 
 
+def test_displaced_with_algorithm_4_restated_by_hand():
+    # stride 2, displaced: the expert at step t runs on the dispatch of step t-1 (its rows, its mask, its
+    # scores) and that result is read at step t+1.  Step 0 synchronous (all pairs); dispatch of step 1
+    # carries slot 0 only, of step 2 both slots, of step 3 slot 0 only.
+    w, k = make_weights(13), 2
+    xs = trajectory(14, 6)
+    T, d = xs[0].shape
+    st = SO.LayerState(T, k, d)
+    ys = []
+    for t, x in enumerate(xs):
+        pol = SO.PolicyArgs(policy=O.REFRESH_ALG4, step_t=t, stride_n=2)
+        ys.append(SO.layer_step(SO.SYNC if t == 0 else SO.DISPLACED, st, x, w, k, pol))
+    r = [routed_layer(x, w, k) for x in xs]
+    h = [ri.h_packed[ri.inv.reshape(-1)].reshape(T, k, d) for ri in r]
+    part = lambda t, j: r[t].s[:, [j]] * h[t][:, j]
+    close = lambda a, b: np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-15)
+    close(ys[1], part(0, 0) + part(0, 1))          # nothing newer has arrived
+    close(ys[2], part(0, 0) + part(0, 1))          # step 1 re-ran the dispatch of step 0
+    close(ys[3], part(1, 0) + part(0, 1))          # step 2 ran the dispatch of step 1: slot 0 only
+    close(ys[4], part(2, 0) + part(2, 1))          # step 3 ran the dispatch of step 2: both slots
+    close(ys[5], part(3, 0) + part(2, 1))          # step 4 ran the dispatch of step 3: slot 0 only
+
+
 def test_shared_experts_are_fresh_under_every_schedule():
     w, k, ns = make_weights(9, n_shared=2), 2, 2
     E = w.Wg.shape[0]
