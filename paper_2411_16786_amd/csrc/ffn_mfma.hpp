@@ -280,4 +280,35 @@ __device__ __forceinline__ void store_slab(const f32x16_v (&half)[TN], char* reg
     __builtin_amdgcn_wave_barrier();
 }
 
+// The same epilogue without the trip through LDS: after the register swap every lane holds 16 bytes of
+// one output row, and stores them itself (a store instruction then touches 32 rows, 32 bytes each).
+template <int TN, bool GELU>
+__device__ __forceinline__ void store_slab_direct(const f32x16_v (&half)[TN], const float4 (&bb)[TN][4],
+                                                  bf16_t* __restrict__ C, int N, int row_first, int row_end,
+                                                  int col_first, int lane, const int32_t* __restrict__ out_index)
+{
+    const int m_local = lane & 31, h = lane >> 5;
+    const int r = row_first + m_local;
+    const int dst = r < row_end ? (out_index ? out_index[r] : r) : -1;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int gp = 0; gp < 2; ++gp) {
+            uint2 packed[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int g = 2 * gp + q;
+                float v0 = half[j][4 * g] + bb[j][g].x, v1 = half[j][4 * g + 1] + bb[j][g].y;
+                float v2 = half[j][4 * g + 2] + bb[j][g].z, v3 = half[j][4 * g + 3] + bb[j][g].w;
+                if (GELU) { v0 = gelu_erf_fast(v0); v1 = gelu_erf_fast(v1); v2 = gelu_erf_fast(v2); v3 = gelu_erf_fast(v3); }
+                packed[q] = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+            }
+            const auto sx = __builtin_amdgcn_permlane32_swap(packed[0].x, packed[1].x, false, false);
+            const auto sy = __builtin_amdgcn_permlane32_swap(packed[0].y, packed[1].y, false, false);
+            const int n = col_first + j * 32 + 16 * gp + 8 * h;
+            if (dst >= 0 && n < N)
+                *reinterpret_cast<u32x4_v*>(C + static_cast<size_t>(dst) * N + n) = u32x4_v{sx[0], sy[0], sx[1], sy[1]};
+        }
+}
+
 }  // namespace dicemoe

@@ -380,9 +380,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     float4 bias_groups[TN][4];
     read_bias_groups<TN>(bias_lds, lane, bias_groups);
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-        store_slab<TN, GELU>(acc[i], region, bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane,
-                             out_index);
+    for (int i = 0; i < TM; ++i) {
+        if (GELU)      // the GELU epilogue is bound by its arithmetic: storing straight from registers saves the LDS trip
+            store_slab_direct<TN, GELU>(acc[i], bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane, out_index);
+        else
+            store_slab<TN, GELU>(acc[i], region, bias_groups, C, N, row0 + wm * WM + i * 32, row_end, col_first, lane,
+                                 out_index);
+    }
 }
 
 template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG = 0, int WGM = 2, int WGN = 2>
