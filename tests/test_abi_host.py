@@ -27,6 +27,34 @@ def test_library_exports_every_declared_entry_point():
     assert sorted(B.EXPORTS) == names
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own, and a C program that only
+    includes it links against the library and reaches the entry points that need no GPU."""
+    import subprocess
+    src = tmp_path / "use_abi.c"
+    src.write_text(
+        '#include "dice_moe.h"\n'
+        '#include <stdio.h>\n'
+        'int main(void) {\n'
+        '    moe_shape s = {64, 64, 256, 4, 5, MOE_F32, 0, 0};   /* k > E */\n'
+        '    moe_ctx* ctx = 0;\n'
+        '    int rc = moe_create(&ctx, &s);\n'
+        '    printf("%d %s\\n", rc, moe_status_string(rc));\n'
+        '    s.k = 2;\n'
+        '    rc = moe_create(&ctx, &s);\n'
+        '    printf("%d %lu\\n", rc, (unsigned long)moe_workspace_bytes(ctx));\n'
+        '    return moe_destroy(ctx);\n'
+        '}\n')
+    inc = os.path.dirname(HEADER)
+    libdir = os.path.dirname(B.LIB_PATH)
+    exe = tmp_path / "use_abi"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, str(src), "-o", str(exe),
+                    "-L", libdir, "-ldicemoe", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out[0] == str(B.MOE_ERR_SHAPE) and out[1] == "MOE_ERR_SHAPE"
+    assert out[2] == "0" and int(out[3]) >= 64 * 2 * 256 * 4
+
+
 def test_struct_layouts_match_the_header():
     src = open(HEADER).read()
     shape_fields = re.search(r"typedef struct \{([^{}]*)\} moe_shape;", src, re.S).group(1)
