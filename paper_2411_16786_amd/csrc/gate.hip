@@ -9,6 +9,7 @@
 // E x TPW partial sums are reduced over the 64 lanes with a fixed butterfly.  Then lane e plays
 // expert e: it ranks its logit against the others and, if it is among the K largest, writes its
 // index and probability.  The kernel is bound by reading x once from HBM.
+#include <type_traits>
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -128,14 +129,35 @@ __global__ __launch_bounds__(256) void gate_kernel(const T* __restrict__ x, cons
     }
 }
 
+// A value of the lane N places away inside the caller's row of 16 lanes (DPP row rotation; N = 1 .. 15
+// visits every other lane of the row once).
+template <int N>
+__device__ __forceinline__ int row_rotate(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, 0x120 + N, 0xF, 0xF, true);
+}
+template <int N>
+__device__ __forceinline__ float row_rotate(float v) {
+    return __builtin_bit_cast(float, row_rotate<N>(__builtin_bit_cast(int, v)));
+}
+template <int N, typename F>
+__device__ __forceinline__ void for_row_rotations(F&& f) {
+    if constexpr (N < 16) {
+        f(std::integral_constant<int, N>{});
+        for_row_rotations<N + 1>(f);
+    }
+}
+
 // bf16 router on the matrix cores.  A workgroup owns 16 tokens; logits[16][E] = x[16][d] . Wg[E][d]^T
 // is a chain of v_mfma_f32_16x16x32_bf16 steps over k, split round robin over the 4 wavefronts
 // (wavefront w takes k-steps w, w+4, ...).  Operands come straight from global memory in MFMA
 // layout: lane l supplies row l%16 (a token for x, an expert for Wg) and the 8 consecutive k
 // values 8*(l/16).. of the step, i.e. one 16-byte load each; all loads of a batch are issued before
 // its MFMAs.  Accumulator register v of lane l is logits[token 4*(l/16)+v][expert l%16].  The four
-// partial sums meet in LDS and are added in wavefront order (fixed, reproducible); then wavefront w
-// finishes tokens 4w..4w+3 with lane e playing expert e (rank by logit, ties to the lower id).
+// partial sums meet in LDS and are added in wavefront order (fixed, reproducible).  With at most 16
+// experts thread (t, e) then finishes logit e of token t: the 16 lanes of a DPP row hold one token and
+// rank, maximum and softmax sum come from rotating the row (no further LDS trip, all 16 tokens at once);
+// with more experts wavefront w finishes tokens 4w..4w+3 with lane e playing expert e.  Rank is by
+// logit, ties to the lower id.
 // U = k-steps per batch and wavefront: the launcher picks it so that one batch covers a wavefront's
 // whole share of the row (a single round trip to memory) whenever that fits in registers.
 template <int NB, int U>
@@ -194,6 +216,52 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const bf16_t* __restrict
 #pragma unroll
         for (int v = 0; v < 4; ++v) part[wave][4 * kq + v][nb * 16 + row] = acc[nb][v];
     __syncthreads();
+    if (NB == 1) {
+        // Up to 16 experts: thread (t, e) = (tid / 16, tid % 16) finishes logit e of token t, so a row of 16
+        // lanes is one token and every lane meets the 15 other logits of its token by rotating the row.
+        const int t = threadIdx.x >> 4, e = threadIdx.x & 15;
+        const bool is_expert = e < E;
+        float z = ((part[0][t][e] + part[1][t][e]) + part[2][t][e]) + part[3][t][e];   // wavefront order, then the bias
+        if (bg && is_expert) z += bg[e];
+        const float z_me = is_expert ? z : -INFINITY;       // padding lanes never outrank an expert
+        float zmax = z_me;
+        int rank = 0;
+        for_row_rotations<1>([&](auto n) {
+            const float z_o = row_rotate<decltype(n)::value>(z_me);
+            const int e_o = row_rotate<decltype(n)::value>(e);
+            zmax = fmaxf(zmax, z_o);
+            rank += (z_o > z_me || (z_o == z_me && e_o < e)) ? 1 : 0;
+        });
+        const float q_me = is_expert ? expf(z_me - zmax) : 0.f;
+        float denom = q_me;
+        for_row_rotations<1>([&](auto n) { denom += row_rotate<decltype(n)::value>(q_me); });
+        const float p_me = q_me / denom;
+        const bool chosen = is_expert && rank < k;
+        float s_me = p_me;
+        if (renorm) {
+            const float c_me = chosen ? p_me : 0.f;
+            float ssum = c_me;
+            for_row_rotations<1>([&](auto n) { ssum += row_rotate<decltype(n)::value>(c_me); });
+            s_me = p_me / ssum;
+        }
+        const int tk = tok0 + t;
+        if (tk < T_tok) {
+            const size_t row = static_cast<size_t>(tk) * (k + n_shared);
+            if (chosen) {
+                scores[row + rank] = s_me;
+                expert_idx[row + rank] = e;
+            }
+            if (e < n_shared) {                             // shared experts: every token, score 1
+                scores[row + k + e] = 1.0f;
+                expert_idx[row + k + e] = E + e;
+            }
+            if (is_expert) {
+                if (probs_all) probs_all[static_cast<size_t>(tk) * E + e] = p_me;
+                if (logits) logits[static_cast<size_t>(tk) * E + e] = z_me;
+            }
+        }
+        return;
+    }
     // logits: the four partial sums in wavefront order, then the bias
     for (int i = threadIdx.x; i < 16 * EP; i += blockDim.x) {
         const int t = i / EP, e = i % EP;
