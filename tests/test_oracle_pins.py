@@ -329,6 +329,10 @@ def test_ablation_variants_of_algorithm_4():
     # the mixer: zero is its fixed point, it is a bijection (no collisions on a sample), and one
     # flipped input bit flips about half of the output bits
     assert O.mix32(0, 0) == 0
+    # published outputs of the MurmurHash3 32-bit finaliser for the inputs 1, 2 and 2^32 - 1 (they fix the
+    # shifts and both multipliers), and the seed enters as seed * 0x9E3779B9 added to the token, mod 2^32
+    assert O.mix32(0, 1) == 0x514E28B7 and O.mix32(0, 2) == 0x30F4C306 and O.mix32(0, 0xFFFFFFFF) == 0x81F16F39
+    assert O.mix32(1, 0) == O.mix32(0, 0x9E3779B9) and O.mix32(3, 5) == O.mix32(0, (3 * 0x9E3779B9 + 5) % 2**32)
     vals = {O.mix32(7, i) for i in range(20000)}
     assert len(vals) == 20000
     flips = [bin(O.mix32(7, i) ^ O.mix32(7, i ^ 1)).count("1") for i in range(2000)]
