@@ -117,3 +117,66 @@ def test_planted_mistake_is_caught_by_a_pin(name, old, new, tmp_path):
     finally:
         O._lib = good
     assert failed_pin is not None, f"planted mistake '{name}' passes every pin"
+
+
+# ---- the schedule oracle (Python): the same check on a copy of its source, run as a module of its own
+SCHEDULE_SRC = os.path.join(os.path.dirname(O.__file__), "schedule_oracle.py")
+
+SCHEDULE_MUTATIONS = [
+    ("interweaved scales after this step's experts arrived",
+     "        y = _scale(st, now.s, pol.use_fresh_scores)\n        # ... the dispatch is waited for within the step, the expert runs on THIS step's rows,\n"
+     "        # and its combine is collected in the next step\n        _expert_and_arrive(st, now, routed, E)\n",
+     "        _expert_and_arrive(st, now, routed, E)\n        y = _scale(st, now.s, pol.use_fresh_scores)\n"),
+    ("displaced experts see this step's dispatch", "_expert_and_arrive(st, st.pending, routed, E)",
+     "_expert_and_arrive(st, now, routed, E)"),
+    ("displaced scales after the arrival",
+     "        y = _scale(st, now.s, pol.use_fresh_scores)\n        _expert_and_arrive(st, st.pending, routed, E)\n",
+     "        _expert_and_arrive(st, st.pending, routed, E)\n        y = _scale(st, now.s, pol.use_fresh_scores)\n"),
+    ("displaced forgets the new dispatch", "        st.pending = now\n", "        pass\n"),
+    ("stale outputs scaled with this step's scores", "s = s_now if use_fresh_scores else st.S",
+     "s = st.S if use_fresh_scores else s_now"),
+    ("arrived scores not stored", "    Sf[disp.perm] = disp.s.reshape(T * k)[disp.perm]\n", ""),
+    ("arrived rows land in packed order", "    Hf[disp.perm] = x_e\n", "    Hf[:len(disp.perm)] = x_e\n"),
+    ("shared experts left out of the asynchronous schedules", "        return y + y_shared\n    if schedule == DISPLACED:",
+     "        return y\n    if schedule == DISPLACED:"),
+    ("shared experts see nothing", "y_shared = O.shared_experts(x, *shared) if n_shared else 0.0", "y_shared = 0.0"),
+    ("no synchronous warm-up", "sched = SYNC if (t < warmup or l in sync_layers) else schedule",
+     "sched = SYNC if (t < warmup - 1 or l in sync_layers) else schedule"),
+    ("Selective Synchronization ignored", "sched = SYNC if (t < warmup or l in sync_layers) else schedule",
+     "sched = SYNC if (t < warmup) else schedule"),
+    ("no residual between layers", "x = (x.astype(np.float64) + y).astype(np.float32)", "x = y.astype(np.float32)"),
+    ("synchronous step leaves no dispatch behind", "        st.pending = Dispatched(r.x_packed, r.offsets, r.perm, r.s, r.mask)",
+     "        st.pending = None"),
+    ("Algorithm 4 not applied when routing", "mask, _ = O.refresh_mask(s, pol.policy, pol.step_t, pol.stride_n, pol.n_units)",
+     "mask, _ = O.refresh_mask(s, O.REFRESH_ALL)"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", SCHEDULE_MUTATIONS, ids=[m[0].replace(" ", "-") for m in SCHEDULE_MUTATIONS])
+def test_planted_schedule_mistake_is_caught_by_a_pin(name, old, new):
+    import types
+
+    from oracle import schedule_oracle as good
+    source = open(SCHEDULE_SRC).read()
+    assert source.count(old) >= 1, f"the text to mutate for '{name}' is no longer in the schedule oracle"
+    mutant = types.ModuleType("oracle.schedule_oracle_mutant")
+    mutant.__package__ = "oracle"
+    mutant.__file__ = SCHEDULE_SRC
+    import sys
+    sys.modules[mutant.__name__] = mutant          # dataclasses look their module up by name
+    failed_pin = None
+    try:
+        exec(compile(source.replace(old, new, 1), SCHEDULE_SRC, "exec"), mutant.__dict__)
+        schedule_pins.SO = mutant
+        for pin_name, call in _pin_calls():
+            if not pin_name.startswith("test_") or getattr(schedule_pins, pin_name.split("[")[0], None) is None:
+                continue
+            try:
+                call()
+            except Exception:
+                failed_pin = pin_name
+                break
+    finally:
+        schedule_pins.SO = good
+        sys.modules.pop(mutant.__name__, None)
+    assert failed_pin is not None, f"planted mistake '{name}' passes every schedule pin"

@@ -182,6 +182,18 @@ def test_stack_fixed_point_selective_sync_and_warmup():
         x_in, y = seen[(t, 0)]
         x_prev, _ = seen[(t - 1, 0)]
         np.testing.assert_allclose(y, routed_layer(x_prev, layers[0], k).y, rtol=1e-13, atol=1e-15)   # shallow: 1 step stale
+    # the stack itself: layer l+1 reads x + y of layer l (kept in float32), the step's result is the
+    # last layer's x + y, and every step starts from the input given for it
+    seen = {}
+    outs, _ = SO.run_stack(xs, layers, k, SO.INTERWEAVED, warmup=1,
+                           record=lambda t, l, x, y: seen.__setitem__((t, l), (x.copy(), y.copy())))
+    for t in range(len(xs)):
+        np.testing.assert_array_equal(seen[(t, 0)][0], xs[t])
+        assert np.abs(seen[(t, 0)][1]).max() > 1e-3           # a residual of nothing would pin nothing
+        for l in range(L):
+            x_l, y_l = seen[(t, l)]
+            nxt = (x_l.astype(np.float64) + y_l).astype(np.float32)
+            np.testing.assert_array_equal(seen[(t, l + 1)][0] if l + 1 < L else outs[t], nxt)
     # errors of the two schedules against the synchronous stack: 1-step staleness hurts less than 2-step
     out_d, _ = SO.run_stack(xs, layers, k, SO.DISPLACED, warmup=1)
     out_i, _ = SO.run_stack(xs, layers, k, SO.INTERWEAVED, warmup=1)
