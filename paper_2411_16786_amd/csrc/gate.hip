@@ -251,9 +251,9 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const bf16_t* __restrict
                 scores[row + rank] = s_me;
                 expert_idx[row + rank] = e;
             }
-            if (e < n_shared) {                             // shared experts: every token, score 1
-                scores[row + k + e] = 1.0f;
-                expert_idx[row + k + e] = E + e;
+            for (int sh = e; sh < n_shared; sh += 16) {     // shared experts: every token, score 1
+                scores[row + k + sh] = 1.0f;
+                expert_idx[row + k + sh] = E + sh;
             }
             if (is_expert) {
                 if (probs_all) probs_all[static_cast<size_t>(tk) * E + e] = p_me;

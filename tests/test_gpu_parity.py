@@ -81,6 +81,27 @@ def test_gate_exact_ties_go_to_the_lower_expert():
     np.testing.assert_array_equal(G.to_np(idx), O.topk(z_gpu.astype(np.float64), k))
 
 
+@pytest.mark.parametrize("dtype,E,k,n_shared", [("bf16", 4, 2, 20), ("bf16", 16, 2, 3), ("bf16", 20, 3, 5), ("f32", 4, 1, 20)])
+def test_gate_writes_every_shared_slot(dtype, E, k, n_shared):
+    # the shared experts' slots follow the k routed ones: expert ids E .. E+n_shared-1, score 1
+    T, d = 50, 64
+    say(f"gate with shared slots: {dtype} E={E} k={k} n_shared={n_shared}")
+    x, Wg, bg, *_ = G.small_inputs(14, T, d, E, 64, dtype, bias=True)
+    ctx = B.Context(T, d, 64, E, k, dtype, n_shared=n_shared)
+    slots = k + n_shared
+    scores = torch.full((T, slots), -3.0, dtype=torch.float32, device=G.DEV)
+    idx = torch.full((T, slots), -3, dtype=torch.int32, device=G.DEV)
+    logits = torch.empty((T, E), dtype=torch.float32, device=G.DEV)
+    ctx.moe_gate(G.to_dev(x, dtype), G.to_dev(Wg, dtype), G.f32_dev(bg), scores, idx, None, logits)
+    torch.cuda.synchronize()
+    idx_gpu, s_gpu, z_gpu = G.to_np(idx), G.to_np(scores), G.to_np(logits)
+    np.testing.assert_array_equal(idx_gpu[:, :k], O.topk(z_gpu.astype(np.float64), k))
+    np.testing.assert_array_equal(idx_gpu[:, k:], np.broadcast_to(E + np.arange(n_shared), (T, n_shared)))
+    np.testing.assert_array_equal(s_gpu[:, k:], 1.0)
+    _, s = O.scores(O.router_logits(x, Wg, bg), idx_gpu[:, :k])
+    np.testing.assert_allclose(s_gpu[:, :k], s, rtol=5e-5, atol=1e-9)
+
+
 # ----------------------------------------------------------------------------- refresh mask
 def gpu_mask(ctx, s_dev, policy):
     T, k = s_dev.shape
