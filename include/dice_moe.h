@@ -34,7 +34,7 @@
  *   - Weights are stored like a linear layer's weight, rows = output features:
  *       Wg[E][d],  W1[E][F][d],  b1[E][F],  W2[E][d][F],  b2[E][d].
  *   - Limits: 1 <= k <= E, E + n_shared <= 64; d % 16 == 0 and F % 16 == 0; for MOE_BF16 also d % 64 == 0 and
- *     F % 64 == 0 (MFMA tile depth); T*k < 2^31 / max(d, F).
+ *     F % 64 == 0 (MFMA tile depth); for MOE_F32 d <= 4096; T*k < 2^31 / max(d, F).
  */
 #ifndef DICE_MOE_H
 #define DICE_MOE_H

@@ -61,6 +61,7 @@ int moe_create(moe_ctx** out, const moe_shape* s)
     if (s->n_shared < 0 || s->k > s->E || s->E + s->n_shared > 64) return MOE_ERR_SHAPE;
     const int mult = (s->dtype == MOE_BF16) ? 64 : 16;
     if (s->d % mult != 0 || s->F % mult != 0) return MOE_ERR_SHAPE;
+    if (s->dtype == MOE_F32 && s->d > 4096) return MOE_ERR_SHAPE;     // the float router holds a row in 16 slices per lane
     const long long rows = static_cast<long long>(s->T_max) * (s->k + s->n_shared);
     const long long widest = s->d > s->F ? s->d : s->F;
     if (rows * widest >= (1ll << 31)) return MOE_ERR_SHAPE;

@@ -74,6 +74,7 @@ def test_struct_layouts_match_the_header():
     (dict(T_max=64, d=60, F=256, E=4, k=2, dtype="f32"), B.MOE_ERR_SHAPE),       # d % 16
     (dict(T_max=64, d=96, F=256, E=4, k=2, dtype="bf16"), B.MOE_ERR_SHAPE),      # d % 64 for bf16
     (dict(T_max=-1, d=64, F=256, E=4, k=2, dtype="f32"), B.MOE_ERR_SHAPE),
+    (dict(T_max=64, d=4112, F=256, E=4, k=2, dtype="f32"), B.MOE_ERR_SHAPE),     # float rows wider than the router holds
     (dict(T_max=64, d=64, F=256, E=4, k=2, dtype="f32", n_shared=2), 0),
     (dict(T_max=64, d=64, F=256, E=4, k=2, dtype="f32", n_shared=-1), B.MOE_ERR_SHAPE),
     (dict(T_max=64, d=64, F=256, E=63, k=2, dtype="f32", n_shared=2), B.MOE_ERR_SHAPE),  # E + shared > 64
