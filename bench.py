@@ -36,6 +36,10 @@ def main():
     ap.add_argument("--refresh-sweep", action="store_true",
                     help="also time the 512px conditional-communication workload (T=8192) at refresh fractions "
                          "25/50/75/100 %% and report it under 'conditional_refresh'")
+    ap.add_argument("--ep-shard", action="store_true",
+                    help="also time the grouped FFN over one expert-parallel shard's receive buffer (16384 rows from "
+                         "four source ranks, four local experts under a Zipf load, d=2048, F=8192) and report it under "
+                         "'ep_shard'")
     ap.add_argument("--packed-dispatch", action="store_true",
                     help="materialise x_packed in moe_dispatch instead of gathering rows in the FFN's operand load")
     ap.add_argument("--n-shared", type=int, default=0,
@@ -252,6 +256,38 @@ def main():
                          "ffn_flops_needed": 4.0 * n_units * c4.k * c4.d * c4.F})
         del buf4, w4
 
+    # ---- optional: the receive side of an expert-parallel shard (segments ordered [source rank][local expert])
+    ep_shard = None
+    if args.ep_shard:
+        ep = WL.make_ep_shard()
+        c5 = ep.cfg
+        rows, W_ranks, E_loc = ep.x_recv.shape[0], ep.recv_counts.shape[0], ep.recv_counts.shape[1]
+        ctx5 = B.Context(rows, c5.d, c5.F, E_loc, 1, "bf16")
+        seg_offsets = torch.empty(W_ranks * E_loc + 1, dtype=torch.int32, device=dev)
+        seg_expert = torch.empty(W_ranks * E_loc, dtype=torch.int32, device=dev)
+        ctx5.moe_ep_segments(torch.from_numpy(np.ascontiguousarray(ep.recv_counts, dtype=np.int32)).to(dev),
+                             seg_offsets, seg_expert)
+        x5, W1_5, W2_5 = up(ep.x_recv), up(ep.W1), up(ep.W2)
+        h5 = torch.empty((rows, c5.d), dtype=torch.bfloat16, device=dev)
+        ws5 = torch.empty(ctx5.workspace_bytes(), dtype=torch.uint8, device=dev)
+        call = lambda: ctx5.moe_expert_ffn(x5, seg_offsets, seg_expert, rows, W1_5, None, W2_5, None, h5, ws5)
+        for _ in range(3):
+            call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        flops5 = 4.0 * rows * c5.d * c5.F
+        ep_shard = {"rows": rows, "segments": W_ranks * E_loc, "rows_per_local_expert": ep.recv_counts.sum(axis=0).tolist(),
+                    "ms_per_call": round(ms, 4), "rows_per_s": round(rows / (ms * 1e-3), 1), "flops": flops5,
+                    "TFLOP/s": round(flops5 / (ms * 1e-3) / 1e12, 1),
+                    "frac_mfma": round(flops5 / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        del x5, W1_5, W2_5, h5, ws5
+
     # ---- the CPU oracle on a bounded sample of the same workload (layer 0, first tokens)
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -307,6 +343,7 @@ def main():
         "cpu_baseline": cpu_baseline,
         "stages": stages,
         "conditional_refresh": cond,
+        "ep_shard": ep_shard,
         "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))
