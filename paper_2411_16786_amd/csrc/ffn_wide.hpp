@@ -224,8 +224,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     constexpr int PART = (QW + SPREAD - 1) / SPREAD;
     constexpr int PER = (PART + NMFMA - 1) / NMFMA;     // loads per MFMA slot; issued in index order, A before W,
                                                         // which is what the PEND counts rely on
-    auto step = [&](int kt, int sa, int sw, auto next_tag, auto pend_tag, auto refa_tag, auto refw_tag, auto cara_tag,
-                    auto carw_tag) {
+    auto step = [&](auto live_tag, int kt, int sa, int sw, auto next_tag, auto pend_tag, auto refa_tag, auto refw_tag,
+                    auto cara_tag, auto carw_tag) {
+        constexpr bool LIVE = decltype(live_tag)::value;
         constexpr bool NEXT = decltype(next_tag)::value;
         constexpr int PEND = decltype(pend_tag)::value;
         constexpr bool REFA = decltype(refa_tag)::value, REFW = decltype(refw_tag)::value;
@@ -246,9 +247,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
             DICEMOE_SCHED_FENCE();
 #pragma unroll
             for (int m = 0; m < NMFMA; ++m) {
-                mfma(set, m);
+                if (LIVE) mfma(set, m);
                 DICEMOE_SCHED_FENCE();
-                if (m < NFRAG) { read_frag(set ^ 1, m, cur_a, cur_w, kk + 1); DICEMOE_SCHED_FENCE(); }
+                if (LIVE && m < NFRAG) { read_frag(set ^ 1, m, cur_a, cur_w, kk + 1); DICEMOE_SCHED_FENCE(); }
                 if ((CARA || CARW) && kk + 1 < SPREAD) {
 #pragma unroll
                     for (int j = 0; j < PER; ++j) {
@@ -271,9 +272,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
         DICEMOE_SCHED_FENCE();
 #pragma unroll
         for (int m = 0; m < NMFMA; ++m) {
-            mfma(1, m);
+            if (LIVE) mfma(1, m);
             DICEMOE_SCHED_FENCE();
-            if (NEXT && m < NFRAG) { read_frag(0, m, nxt_a, nxt_w, 0); DICEMOE_SCHED_FENCE(); }
+            if (LIVE && NEXT && m < NFRAG) { read_frag(0, m, nxt_a, nxt_w, 0); DICEMOE_SCHED_FENCE(); }
             if (REFA || REFW) {
 #pragma unroll
                 for (int j = 0; j < PER; ++j) {
@@ -286,63 +287,73 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     const std::true_type yes{};
     const std::false_type no{};
     const std::integral_constant<int, 0> p0{};
-    int sa = 0, sw = 0;
-    auto advance = [&]() { sa = (sa + 1 == AST) ? 0 : sa + 1; sw = (sw + 1 == WST) ? 0 : sw + 1; };
-    // Which loads are younger than those of stage kt+1 at the barrier of step kt follows from the issue
-    // order: prologue W0.. then A0..; refill of step j: A(j+AST) then W(j+WST).
-    if (AST == 2 && WST == 2) {
-        if (nk == 1) {
-            step(0, 0, 0, no, p0, no, no, no, no);
-        } else {
-            if (nk > 2) step(0, 0, 0, yes, p0, yes, yes, no, no); else step(0, 0, 0, yes, p0, no, no, no, no);
+    // A wavefront whose 32 TM rows all lie past the end of the segment (the ragged last row tile of an
+    // expert) has nothing to compute: it keeps its share of the loads, the waits and the barriers, and
+    // leaves the matrix pipe of its SIMD to the wavefront it shares it with.
+    const bool live = row0 + wm * WM < row_end;
+    auto run_steps = [&](auto live_tag) {
+        int sa = 0, sw = 0;
+        auto advance = [&]() { sa = (sa + 1 == AST) ? 0 : sa + 1; sw = (sw + 1 == WST) ? 0 : sw + 1; };
+        // Which loads are younger than those of stage kt+1 at the barrier of step kt follows from the issue
+        // order: prologue W0.. then A0..; refill of step j: A(j+AST) then W(j+WST).
+        if (AST == 2 && WST == 2) {
+            if (nk == 1) {
+                step(live_tag, 0, 0, 0, no, p0, no, no, no, no);
+            } else {
+                if (nk > 2) step(live_tag, 0, 0, 0, yes, p0, yes, yes, no, no); else step(live_tag, 0, 0, 0, yes, p0, no, no, no, no);
+                advance();
+                int kt = 1;
+                for (; kt + 2 < nk; ++kt) { step(live_tag, kt, sa, sw, yes, p0, yes, yes, yes, yes); advance(); }
+                if (nk > 2) { step(live_tag, kt, sa, sw, yes, p0, no, no, yes, yes); advance(); ++kt; }
+                step(live_tag, kt, sa, sw, no, p0, no, no, no, no);
+            }
+        } else if (AST == 2 && WST == 3) {
+            const std::integral_constant<int, QB> pw{};      // the W part of the previous step's refill
+            step(live_tag, 0, 0, 0, yes, p0, yes, yes, no, no);
             advance();
             int kt = 1;
-            for (; kt + 2 < nk; ++kt) { step(kt, sa, sw, yes, p0, yes, yes, yes, yes); advance(); }
-            if (nk > 2) { step(kt, sa, sw, yes, p0, no, no, yes, yes); advance(); ++kt; }
-            step(kt, sa, sw, no, p0, no, no, no, no);
+            for (; kt + 3 < nk; ++kt) { step(live_tag, kt, sa, sw, yes, pw, yes, yes, yes, yes); advance(); }
+            step(live_tag, kt, sa, sw, yes, pw, yes, no, yes, yes); advance(); ++kt;      // kt = nk-3: A(nk-1) is the last refill
+            step(live_tag, kt, sa, sw, yes, p0, no, no, yes, no); advance(); ++kt;        // kt = nk-2
+            step(live_tag, kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
+        } else if (AST == 4 && WST == 4) {
+            // three stages in flight per operand.  Loads younger than stage kt+1 at the barrier of step kt:
+            // step 0: A2, A3 of the prologue; step 1: A3 and refill 0; later: the last two refills
+            const std::integral_constant<int, 2 * QA> p2a{};
+            const std::integral_constant<int, QA + QW> paq{};
+            const std::integral_constant<int, 2 * QW> p2q{};
+            const std::integral_constant<int, QW> pq{};
+            step(live_tag, 0, 0, 0, yes, p2a, yes, yes, no, no);
+            advance();
+            step(live_tag, 1, sa, sw, yes, paq, yes, yes, yes, yes);
+            advance();
+            int kt = 2;
+            for (; kt + 4 < nk; ++kt) { step(live_tag, kt, sa, sw, yes, p2q, yes, yes, yes, yes); advance(); }
+            step(live_tag, kt, sa, sw, yes, p2q, no, no, yes, yes); advance(); ++kt;      // kt = nk-4: the last refill was issued at nk-5
+            step(live_tag, kt, sa, sw, yes, pq, no, no, no, no); advance(); ++kt;         // kt = nk-3
+            step(live_tag, kt, sa, sw, yes, p0, no, no, no, no); advance(); ++kt;         // kt = nk-2
+            step(live_tag, kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
+        } else {
+            const std::integral_constant<int, QA> pa{};      // step 0: the prologue issued the A parts last
+            const std::integral_constant<int, QW> pq{};      // the previous step's whole refill
+            step(live_tag, 0, 0, 0, yes, pa, yes, yes, no, no);
+            advance();
+            int kt = 1;
+            for (; kt + 3 < nk; ++kt) { step(live_tag, kt, sa, sw, yes, pq, yes, yes, yes, yes); advance(); }
+            step(live_tag, kt, sa, sw, yes, pq, no, no, yes, yes); advance(); ++kt;       // kt = nk-3
+            step(live_tag, kt, sa, sw, yes, p0, no, no, no, no); advance(); ++kt;         // kt = nk-2
+            step(live_tag, kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
         }
-    } else if (AST == 2 && WST == 3) {
-        const std::integral_constant<int, QB> pw{};      // the W part of the previous step's refill
-        step(0, 0, 0, yes, p0, yes, yes, no, no);
-        advance();
-        int kt = 1;
-        for (; kt + 3 < nk; ++kt) { step(kt, sa, sw, yes, pw, yes, yes, yes, yes); advance(); }
-        step(kt, sa, sw, yes, pw, yes, no, yes, yes); advance(); ++kt;      // kt = nk-3: A(nk-1) is the last refill
-        step(kt, sa, sw, yes, p0, no, no, yes, no); advance(); ++kt;        // kt = nk-2
-        step(kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
-    } else if (AST == 4 && WST == 4) {
-        // three stages in flight per operand.  Loads younger than stage kt+1 at the barrier of step kt:
-        // step 0: A2, A3 of the prologue; step 1: A3 and refill 0; later: the last two refills
-        const std::integral_constant<int, 2 * QA> p2a{};
-        const std::integral_constant<int, QA + QW> paq{};
-        const std::integral_constant<int, 2 * QW> p2q{};
-        const std::integral_constant<int, QW> pq{};
-        step(0, 0, 0, yes, p2a, yes, yes, no, no);
-        advance();
-        step(1, sa, sw, yes, paq, yes, yes, yes, yes);
-        advance();
-        int kt = 2;
-        for (; kt + 4 < nk; ++kt) { step(kt, sa, sw, yes, p2q, yes, yes, yes, yes); advance(); }
-        step(kt, sa, sw, yes, p2q, no, no, yes, yes); advance(); ++kt;      // kt = nk-4: the last refill was issued at nk-5
-        step(kt, sa, sw, yes, pq, no, no, no, no); advance(); ++kt;         // kt = nk-3
-        step(kt, sa, sw, yes, p0, no, no, no, no); advance(); ++kt;         // kt = nk-2
-        step(kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
-    } else {
-        const std::integral_constant<int, QA> pa{};      // step 0: the prologue issued the A parts last
-        const std::integral_constant<int, QW> pq{};      // the previous step's whole refill
-        step(0, 0, 0, yes, pa, yes, yes, no, no);
-        advance();
-        int kt = 1;
-        for (; kt + 3 < nk; ++kt) { step(kt, sa, sw, yes, pq, yes, yes, yes, yes); advance(); }
-        step(kt, sa, sw, yes, pq, no, no, yes, yes); advance(); ++kt;       // kt = nk-3
-        step(kt, sa, sw, yes, p0, no, no, no, no); advance(); ++kt;         // kt = nk-2
-        step(kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
-    }
+
+    };
+    if (live) run_steps(yes);
+    else run_steps(no);
 
     // ---- epilogue: the stage buffers are free once every wavefront is past its last fragment read
     wait_vmcnt<0>();
     wait_lgkmcnt<0>();
     block_barrier();
+    if (!live) return;
     if (DIAG & 1) {
         float s = 0.f;
 #pragma unroll
