@@ -29,14 +29,17 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_wave_barrier();
 }
 
-// lanes of this wave that are live and hold the same expert id as the calling lane
-__device__ __forceinline__ uint64_t same_expert_peers(bool live, int e) {
+// lanes of this wave that are live and hold the same expert id as the calling lane; nbits = number of
+// bits an expert id can have (ballots are scalar work, and one scalar unit serves the whole workgroup)
+__device__ __forceinline__ uint64_t same_expert_peers(bool live, int e, int nbits) {
     uint64_t peers = __ballot(live);
 #pragma unroll
     for (int b = 0; b < 6; ++b) {
-        const bool bit = (e >> b) & 1;
-        const uint64_t bb = __ballot(bit);
-        peers &= bit ? bb : ~bb;
+        if (b < nbits) {                          // uniform
+            const bool bit = (e >> b) & 1;
+            const uint64_t bb = __ballot(bit);
+            peers &= bit ? bb : ~bb;
+        }
     }
     return peers;
 }
@@ -89,6 +92,7 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
     const int tid = threadIdx.x;
     const int wave = tid / kWave;
     const int lane = lane_id();
+    const int nbits = E > 1 ? 32 - __builtin_clz(static_cast<unsigned>(E - 1)) : 0;
     const int L = (((N + kIdxWaves - 1) / kIdxWaves) + kWave - 1) / kWave * kWave;
     const int lo = wave * L;
     const int hi = (lo + L < N) ? lo + L : N;
@@ -113,7 +117,7 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
                 for (int u = 0; u < kChunk; ++u) {
                     const bool live = ev_keep[c][u] >= 0;
                     const int e = live ? ev_keep[c][u] : 0;
-                    const uint64_t peers = same_expert_peers(live, e);
+                    const uint64_t peers = same_expert_peers(live, e, nbits);
                     const int before = __popcll(peers & lanemask_lt());
                     const int run = wave_run[wave][e];     // every peer reads the same running count ...
                     rank_keep[c][u] = run + before;
@@ -134,7 +138,7 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
             for (int u = 0; u < kChunk; ++u) {
                 const bool live = ev[u] >= 0;
                 const int e = live ? ev[u] : 0;
-                const uint64_t peers = same_expert_peers(live, e);
+                const uint64_t peers = same_expert_peers(live, e, nbits);
                 if (live && (peers & lanemask_lt()) == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
                 wave_sync();
             }
@@ -191,7 +195,7 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32
                 const int p = c0 + u * kWave + lane;
                 const bool live = ev[u] >= 0;
                 const int e = live ? ev[u] : 0;
-                const uint64_t peers = same_expert_peers(live, e);
+                const uint64_t peers = same_expert_peers(live, e, nbits);
                 const int before = __popcll(peers & lanemask_lt());
                 int r = -1;
                 if (live) r = s_off[e] + wave_run[wave][e] + before;
