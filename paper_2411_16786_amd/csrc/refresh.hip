@@ -61,10 +61,10 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
 {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sfx[2][256];
-    __shared__ uint32_t s_prefix, s_remaining;
+    __shared__ uint32_t s_prefix, s_remaining, s_equal;
     __shared__ int wave_cnt[kSelWaves];
     const int tid = threadIdx.x;
-    if (tid == 0) { *n_refresh = n_value; s_prefix = 0; s_remaining = static_cast<uint32_t>(m); }
+    if (tid == 0) { *n_refresh = n_value; s_prefix = 0; s_remaining = static_cast<uint32_t>(m); s_equal = 0; }
 
     const bool need_select = (m > 0 && m < T_tok);
     if (need_select) {
@@ -98,6 +98,7 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
                 if (above < rem && rem <= above + hist[tid]) {   // exactly one digit satisfies this
                     s_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
                     s_remaining = rem - above;
+                    s_equal = hist[tid];            // after the last pass: the keys equal to the threshold
                 }
             }
             __syncthreads();
@@ -106,6 +107,8 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
     __syncthreads();
     const uint32_t thr = s_prefix;
     const int admit_equal = static_cast<int>(s_remaining);  // keys equal to thr to admit, in index order
+    // every key equal to the threshold is admitted (no tie straddles the cut, the usual case): no ordering needed
+    const bool all_equal_in = need_select && admit_equal == static_cast<int>(s_equal);
     const int wave = tid / kWave;
     int running = 0;
     for (int base = 0; base < T_tok; base += kSelThreads) {
@@ -114,6 +117,8 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
         bool sel;
         if (!need_select) {
             sel = (m > 0);
+        } else if (all_equal_in) {
+            sel = valid && order_key(scores[static_cast<size_t>(i) * kc + slot]) >= thr;
         } else {
             const uint32_t key = valid ? order_key(scores[static_cast<size_t>(i) * kc + slot]) : 0u;
             const bool eq = valid && key == thr;
