@@ -146,7 +146,10 @@ class Context:
     def __del__(self):
         h = getattr(self, "_h", None)
         if h is not None and h.value:
-            lib().moe_destroy(h)
+            try:
+                lib().moe_destroy(h)
+            except Exception:          # interpreter shutdown: the module's globals may be gone already
+                pass
             self._h = ctypes.c_void_p()
 
     def _check(self, rc: int):
