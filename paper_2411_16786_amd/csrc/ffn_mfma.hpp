@@ -93,16 +93,17 @@ __device__ __forceinline__ bool find_row_tile(const int32_t* __restrict__ seg_of
 __device__ __forceinline__ bool find_tile_by_expert(const int32_t* __restrict__ seg_offsets,
                                                     const int32_t* __restrict__ seg_expert, int n_seg, int BM,
                                                     int n_tiles_n, int group_m, int block, int& seg, int& row0,
-                                                    int& row_end, int& tile_n)
+                                                    int& row_end, int& tile_n, int& expert)
 {
     // n_seg <= 64: lane g holds segment g (one vector load instead of a walk of dependent scalar loads);
     // the uniform loops below pick the entries out with readlane
     const int lane = threadIdx.x & 63;
-    int my_begin = 0, my_end = 0, my_home = 8;
+    int my_begin = 0, my_end = 0, my_home = 8, my_expert = 0;
     if (lane < n_seg) {
         my_begin = seg_offsets[lane];
         my_end = seg_offsets[lane + 1];
-        my_home = seg_expert[lane] & 7;
+        my_expert = seg_expert[lane];
+        my_home = my_expert & 7;
     }
     const int my_nt = (my_end - my_begin + BM - 1) / BM;
     const int x = block & 7, s = block >> 3;
@@ -157,6 +158,7 @@ __device__ __forceinline__ bool find_tile_by_expert(const int32_t* __restrict__ 
             seg = g;
             row0 = __builtin_amdgcn_readlane(my_begin, g) + tile_m * BM;
             row_end = __builtin_amdgcn_readlane(my_end, g);
+            expert = __builtin_amdgcn_readlane(my_expert, g);      // (no second, dependent trip to memory for it)
             return true;
         }
         idx -= tiles;

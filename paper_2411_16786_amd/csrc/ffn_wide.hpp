@@ -59,10 +59,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     char* const w_lds = smem + AST * ABYTES;
 
     // ---- which tile (bands of GROUP_M row tiles, XCD x takes the x-th eighth of the sequence)
-    int seg, row0, row_end, tile_n;
+    int seg, row0, row_end, tile_n, e = -1;
     if (by_expert) {
         if (!find_tile_by_expert(seg_offsets, seg_expert, n_seg, BM, n_tiles_n, GROUP_M, blockIdx.x, seg, row0, row_end,
-                                 tile_n))
+                                 tile_n, e))
             return;
     } else {
         const int t = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
         if (seg + row0 + row_end + tile_n == -12345) C[0] = 1;
         return;
     }
-    const int e = seg_expert[seg];
+    if (!by_expert) e = seg_expert[seg];
     const int n0 = tile_n * BN;
 
     const int tid = threadIdx.x;
