@@ -140,12 +140,26 @@ int moe_gate(moe_ctx* ctx, const void* x, const void* Wg, const float* bg, int32
 
 /* Conditional Communication decision (Algorithm 4 and its fraction forms, see moe_policy_kind).
  * Ordering is exact on the float bit patterns of `scores`; equal scores go to the lower token.
- *   in : scores[T][k], expert_idx[T][k] (unused by the current policies, may be NULL)
+ *   in : scores[T][k] (read by the FRACTION policies only; the others accept NULL);
+ *        expert_idx[T][k]: no current policy reads it, NULL is accepted
  *   out: mask[T][k] uint8 (1 = refresh), n_refresh[1] int32 on the device
- * workspace: moe_workspace_bytes(); used by the FRACTION policies only. */
+ * workspace: no current policy uses it, NULL is accepted (the argument keeps the call's shape
+ * stable for policies that need scratch). */
 int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* expert_idx,
                             int32_t T, const moe_policy* policy, uint8_t* mask,
                             int32_t* n_refresh, void* workspace, void* stream);
+
+/* Number of pairs that `policy` refreshes among T tokens, known on the host without reading the
+ * mask back (Algorithm 4: slot 0 of every token always, the other slots on steps with
+ * step_t % stride_n == 0; the fraction forms refresh exactly n_units tokens or pairs; shared-expert
+ * slots are refreshed for every token in every step).  It is the value moe_conditional_refresh
+ * writes to n_refresh, and the bound max_rows that sizes the expert FFN launch of that step.
+ *   in : policy (host), T
+ *   out: n_pairs (host): refreshed pairs, shared-expert slots included; n_routed (host, may be
+ *        NULL): the routed ones among them (n_pairs - T * n_shared)
+ * Nothing is launched.  MOE_ERR_POLICY for fields out of range, as in moe_conditional_refresh. */
+int moe_policy_refreshed_pairs(moe_ctx* ctx, const moe_policy* policy, int32_t T, int32_t* n_pairs,
+                               int32_t* n_routed);
 
 /* Dispatch on one device (Algorithm 1, dispatch): a stable counting sort of the refreshed pairs
  * by expert id and a row gather into an expert-contiguous buffer.  With experts partitioned in

@@ -26,7 +26,7 @@ MOE_ERR_NULL, MOE_ERR_SHAPE, MOE_ERR_DTYPE, MOE_ERR_POLICY = -1, -2, -3, -4
 MOE_ERR_WORKSPACE, MOE_ERR_CACHE_COLD, MOE_ERR_HIP = -5, -6, -7
 
 EXPORTS = ["moe_create", "moe_destroy", "moe_workspace_bytes", "moe_last_error", "moe_status_string",
-           "moe_gate", "moe_conditional_refresh", "moe_dispatch", "moe_expert_ffn", "moe_expert_ffn_rows",
+           "moe_gate", "moe_policy_refreshed_pairs", "moe_conditional_refresh", "moe_dispatch", "moe_expert_ffn", "moe_expert_ffn_rows",
            "moe_expert_ffn_commit", "moe_combine", "moe_ep_segments"]
 
 
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.moe_status_string.argtypes = [ctypes.c_int]
         L.moe_status_string.restype = ctypes.c_char_p
         L.moe_gate.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+        L.moe_policy_refreshed_pairs.argtypes = [vp, ctypes.POINTER(MoePolicy), i32, ctypes.POINTER(i32),
+                                                 ctypes.POINTER(i32)]
         L.moe_conditional_refresh.argtypes = [vp, vp, vp, i32, ctypes.POINTER(MoePolicy), vp, vp, vp, vp]
         L.moe_dispatch.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
@@ -107,24 +109,6 @@ class Policy:
     def c(self) -> MoePolicy:
         return MoePolicy(self.kind, self.step_t, self.stride_n, self.n_units, int(self.use_fresh_scores))
 
-    def refreshed_pairs(self, T: int, k: int, n_shared: int = 0) -> int:
-        """Number of (token, slot) pairs this policy refreshes among T tokens.  Every policy fixes it
-        from its parameters alone (Algorithm 4: slot 0 always, the other slots on steps with
-        t mod n == 0; shared-expert slots always), so the host knows it without reading the mask
-        back; it sizes the FFN launch."""
-        shared = T * n_shared
-        if self.kind == REFRESH_ALL:
-            return T * k + shared
-        if self.kind == REFRESH_NONE:
-            return shared
-        if self.kind in (REFRESH_ALG4, REFRESH_ALG4_HIGH, REFRESH_ALG4_RANDOM):
-            return (T * k if self.step_t % self.stride_n == 0 else T) + shared
-        if self.kind == REFRESH_FRACTION_TOKEN:
-            return min(max(self.n_units, 0), T) * k + shared
-        if self.kind == REFRESH_FRACTION_PAIR:
-            return min(max(self.n_units, 0), T * k) + shared
-        raise ValueError("unknown refresh policy %r" % (self.kind,))
-
 
 class Context:
     """Owns one ``moe_ctx``; methods carry the names of the C entry points."""
@@ -158,6 +142,15 @@ class Context:
 
     def workspace_bytes(self) -> int:
         return lib().moe_workspace_bytes(self._h)
+
+    def moe_policy_refreshed_pairs(self, policy: Policy, T: int):
+        """(refreshed pairs incl. shared-expert slots, routed ones among them) for T tokens, from the
+        library (Algorithm 4's count is the library's arithmetic, not the binding's)."""
+        pol = policy.c()
+        n_pairs, n_routed = ctypes.c_int32(), ctypes.c_int32()
+        self._check(lib().moe_policy_refreshed_pairs(self._h, ctypes.byref(pol), T, ctypes.byref(n_pairs),
+                                                     ctypes.byref(n_routed)))
+        return n_pairs.value, n_routed.value
 
     def moe_gate(self, x, Wg, bg, scores, expert_idx, probs_all=None, logits=None):
         T = x.shape[0]
@@ -267,7 +260,7 @@ def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2
     T = x.shape[0]
     N = T * ctx.slots
     if max_rows is None and policy is not None:
-        max_rows = policy.refreshed_pairs(T, ctx.k, ctx.n_shared)
+        max_rows = ctx.moe_policy_refreshed_pairs(policy, T)[0]
     ctx.moe_gate(x, Wg, bg, buf.scores[:T], buf.expert_idx[:T], buf.probs, buf.logits)
     mask = None
     if policy is not None:

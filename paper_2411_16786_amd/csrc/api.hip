@@ -48,6 +48,38 @@ int check_T(moe_ctx* ctx, int32_t T)
     return MOE_OK;
 }
 
+// Validates a refresh policy for T tokens and counts the routed pairs it refreshes (Algorithm 4:
+// slot 0 always, the other slots when step_t % stride_n == 0; the fraction forms by definition).
+int policy_routed_pairs(moe_ctx* ctx, const moe_policy* policy, int32_t T, int32_t* routed)
+{
+    const int k = ctx->shape.k;
+    const long N = static_cast<long>(T) * k;
+    switch (policy->kind) {
+    case MOE_REFRESH_ALL: *routed = static_cast<int32_t>(N); return MOE_OK;
+    case MOE_REFRESH_NONE: *routed = 0; return MOE_OK;
+    case MOE_REFRESH_ALG4:
+    case MOE_REFRESH_ALG4_HIGH:
+    case MOE_REFRESH_ALG4_RANDOM:
+        if (policy->stride_n < 1 || policy->step_t < 0)
+            return fail(ctx, MOE_ERR_POLICY, "ALG4 needs step_t >= 0 and stride_n >= 1 (got %ld, %ld)",
+                        policy->step_t, policy->stride_n);
+        *routed = (policy->step_t % policy->stride_n == 0) ? static_cast<int32_t>(N) : T;
+        return MOE_OK;
+    case MOE_REFRESH_FRACTION_TOKEN:
+        if (policy->n_units < 0 || policy->n_units > T)
+            return fail(ctx, MOE_ERR_POLICY, "FRACTION_TOKEN n_units=%ld outside 0..T=%ld", policy->n_units, T);
+        *routed = policy->n_units * k;
+        return MOE_OK;
+    case MOE_REFRESH_FRACTION_PAIR:
+        if (policy->n_units < 0 || policy->n_units > N)
+            return fail(ctx, MOE_ERR_POLICY, "FRACTION_PAIR n_units=%ld outside 0..T*k=%ld", policy->n_units, N);
+        *routed = policy->n_units;
+        return MOE_OK;
+    default:
+        return fail(ctx, MOE_ERR_POLICY, "unknown policy kind %ld", policy->kind);
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -119,57 +151,65 @@ int moe_gate(moe_ctx* ctx, const void* x, const void* Wg, const float* bg, int32
                       "moe_gate");
 }
 
+int moe_policy_refreshed_pairs(moe_ctx* ctx, const moe_policy* policy, int32_t T, int32_t* n_pairs,
+                               int32_t* n_routed)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (int rc = check_T(ctx, T)) return rc;
+    if (!policy || !n_pairs) return fail(ctx, MOE_ERR_NULL, "moe_policy_refreshed_pairs: null pointer");
+    int32_t routed = 0;
+    if (int rc = policy_routed_pairs(ctx, policy, T, &routed)) return rc;
+    *n_pairs = routed + T * ctx->shape.n_shared;
+    if (n_routed) *n_routed = routed;
+    return MOE_OK;
+}
+
 int moe_conditional_refresh(moe_ctx* ctx, const float* scores, const int32_t* expert_idx, int32_t T,
                             const moe_policy* policy, uint8_t* mask, int32_t* n_refresh, void* workspace,
                             void* stream)
 {
-    (void)expert_idx;
+    (void)expert_idx;      // no current policy reads the expert ids or needs scratch (see the header)
     (void)workspace;
     if (!ctx) return MOE_ERR_NULL;
     if (int rc = check_T(ctx, T)) return rc;
     if (!policy || !mask || !n_refresh) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: null pointer");
+    int32_t routed = 0;
+    if (int rc = policy_routed_pairs(ctx, policy, T, &routed)) return rc;
     const moe_shape& s = ctx->shape;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const int n_value = routed + T * s.n_shared;       // what the device-side n_refresh receives
     const long N = static_cast<long>(T) * s.k;
     switch (policy->kind) {
     case MOE_REFRESH_ALL:
     case MOE_REFRESH_NONE:
-        return hip_result(ctx, launch_refresh_simple(policy->kind, T, s.k, s.n_shared, 0, 1, 0u, mask, n_refresh, st),
+        return hip_result(ctx, launch_refresh_simple(policy->kind, T, s.k, s.n_shared, 0, 0u, n_value, mask, n_refresh, st),
                           "moe_conditional_refresh");
     case MOE_REFRESH_ALG4:
     case MOE_REFRESH_ALG4_HIGH:
     case MOE_REFRESH_ALG4_RANDOM:
-        if (policy->stride_n < 1 || policy->step_t < 0)
-            return fail(ctx, MOE_ERR_POLICY, "ALG4 needs step_t >= 0 and stride_n >= 1 (got %ld, %ld)",
-                        policy->step_t, policy->stride_n);
         return hip_result(ctx,
-                          launch_refresh_simple(policy->kind, T, s.k, s.n_shared, policy->step_t, policy->stride_n,
-                                                static_cast<uint32_t>(policy->n_units), mask, n_refresh, st),
+                          launch_refresh_simple(policy->kind, T, s.k, s.n_shared,
+                                                policy->step_t % policy->stride_n != 0 ? 1 : 0,
+                                                static_cast<uint32_t>(policy->n_units), n_value, mask, n_refresh, st),
                           "moe_conditional_refresh");
     case MOE_REFRESH_FRACTION_TOKEN:
-        if (policy->n_units < 0 || policy->n_units > T)
-            return fail(ctx, MOE_ERR_POLICY, "FRACTION_TOKEN n_units=%ld outside 0..T=%ld", policy->n_units, T);
         if (!scores) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: scores is null");
         return hip_result(ctx,
-                          launch_refresh_select(scores, T, s.k, s.n_shared, 0, policy->n_units, true, policy->n_units * s.k,
-                                                mask, n_refresh, st),
+                          launch_refresh_select(scores, T, s.k, s.n_shared, 0, policy->n_units, true, n_value, mask,
+                                                n_refresh, st),
                           "moe_conditional_refresh");
-    case MOE_REFRESH_FRACTION_PAIR: {
-        if (policy->n_units < 0 || policy->n_units > N)
-            return fail(ctx, MOE_ERR_POLICY, "FRACTION_PAIR n_units=%ld outside 0..T*k=%ld", policy->n_units, N);
+    default: {      // MOE_REFRESH_FRACTION_PAIR (policy_routed_pairs has rejected every other kind)
         if (!scores) return fail(ctx, MOE_ERR_NULL, "moe_conditional_refresh: scores is null");
         if (policy->n_units == N)
-            return hip_result(ctx, launch_refresh_simple(MOE_REFRESH_ALL, T, s.k, s.n_shared, 0, 1, 0u, mask, n_refresh, st),
+            return hip_result(ctx, launch_refresh_simple(MOE_REFRESH_ALL, T, s.k, s.n_shared, 0, 0u, n_value, mask, n_refresh, st),
                               "moe_conditional_refresh");
         // slots before `slot` are refreshed for every token, slot `slot` for its m best tokens
         const int slot = T > 0 ? policy->n_units / T : 0;
         const int m = T > 0 ? policy->n_units % T : 0;
         return hip_result(ctx,
-                          launch_refresh_select(scores, T, s.k, s.n_shared, slot, m, false, policy->n_units, mask, n_refresh, st),
+                          launch_refresh_select(scores, T, s.k, s.n_shared, slot, m, false, n_value, mask, n_refresh, st),
                           "moe_conditional_refresh");
     }
-    default:
-        return fail(ctx, MOE_ERR_POLICY, "unknown policy kind %ld", policy->kind);
     }
 }
 

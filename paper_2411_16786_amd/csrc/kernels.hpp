@@ -11,16 +11,16 @@ hipError_t launch_gate(bool bf16, const void* x, const void* Wg, const float* bg
                        int n_shared, int renorm, float* scores, int32_t* idx, float* probs, float* logits,
                        hipStream_t stream);
 
-// kind: 0 all, 1 Algorithm 4, 4 none (elementwise policies).  mask has k + n_shared columns; the
-// shared slots are refreshed under every policy
-hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int step_t, int stride_n, uint32_t seed,
+// kind: 0 all, 1 / 5 / 6 Algorithm 4 and its ablation variants, 4 none (elementwise policies); off_step:
+// step_t % stride_n != 0.  mask has k + n_shared columns; the shared slots are refreshed under every
+// policy.  n_value is written to n_refresh (the refreshed pairs, shared slots included).
+hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int off_step, uint32_t seed, int n_value,
                                  uint8_t* mask, int32_t* n_refresh, hipStream_t stream);
 // exact top-m selection of tokens by scores[i*k + slot] (descending, ties to the lower token);
 // token_mode: selected tokens get all k slots; otherwise slots < slot are all refreshed, slot
 // `slot` follows the selection and later slots are not refreshed
-// (n_refresh_value counts routed pairs; the shared slots are added here)
 hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int n_shared, int slot, int m,
-                                 bool token_mode, int n_refresh_value, uint8_t* mask, int32_t* n_refresh,
+                                 bool token_mode, int n_value, uint8_t* mask, int32_t* n_refresh,
                                  hipStream_t stream);
 
 hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const uint8_t* mask, int T_tok, int d,

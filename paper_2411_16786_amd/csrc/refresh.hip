@@ -148,16 +148,11 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
     }
 }
 
-hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int step_t, int stride_n, uint32_t seed,
+hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int off_step, uint32_t seed, int n_value,
                                  uint8_t* mask, int32_t* n_refresh, hipStream_t stream)
 {
     const int kc = k + n_shared;
     const int N = T_tok * kc;
-    int off_step = 0, n_value = 0;
-    if (kind == 0) n_value = T_tok * k;
-    else if (kind == 4) n_value = 0;
-    else { off_step = (step_t % stride_n) != 0; n_value = off_step ? T_tok : T_tok * k; }
-    n_value += T_tok * n_shared;
     const int blocks = N > 0 ? (N + 255) / 256 : 1;
     hipLaunchKernelGGL(refresh_simple_kernel, dim3(blocks), dim3(256), 0, stream, kind, N, kc, k, off_step, seed,
                        mask, n_refresh, n_value);
@@ -165,11 +160,11 @@ hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int s
 }
 
 hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int n_shared, int slot, int m,
-                                 bool token_mode, int n_refresh_value, uint8_t* mask, int32_t* n_refresh,
+                                 bool token_mode, int n_value, uint8_t* mask, int32_t* n_refresh,
                                  hipStream_t stream)
 {
     hipLaunchKernelGGL(refresh_select_kernel, dim3(1), dim3(kSelThreads), 0, stream, scores, T_tok, k + n_shared, k,
-                       slot, m, token_mode ? 1 : 0, n_refresh_value + T_tok * n_shared, mask, n_refresh);
+                       slot, m, token_mode ? 1 : 0, n_value, mask, n_refresh);
     return hipGetLastError();
 }
 

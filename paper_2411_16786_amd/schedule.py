@@ -78,10 +78,10 @@ def moe_layer_step(schedule: str, st: LayerState, x, Wg, bg, W1, b1, W2, b2, pol
         # Algorithm 1 with Algorithm 4's cache: the combine writes refreshed pairs through to H / S.
         # The dispatch is materialised when a displaced step may follow (it waits on this dispatch).
         y = B.moe_layer_forward(ctx, buf, x, Wg, bg, W1, b1, W2, b2, policy, fuse_gather=len(st.bufs) == 1)
-        st.pending = (buf, T, policy.refreshed_pairs(T, k, 0))
+        st.pending = (buf, T, ctx.moe_policy_refreshed_pairs(policy, T)[1])
         return y
 
-    rows_routed = policy.refreshed_pairs(T, k, 0)
+    rows_routed = ctx.moe_policy_refreshed_pairs(policy, T)[1]
     ctx.moe_gate(x, Wg, bg, buf.scores[:T], buf.expert_idx[:T], buf.probs, buf.logits)
     ctx.moe_conditional_refresh(buf.scores[:T], buf.expert_idx[:T], policy, buf.mask[:T], buf.n_refresh, buf.workspace)
     packed = buf.x_packed if schedule == DISPLACED else None

@@ -154,13 +154,16 @@ def test_binding_refuses_cpu_tensors():
 
 
 def test_policy_row_count_matches_the_oracle_mask():
-    """The binding sizes the FFN launch from the policy alone; the count it derives must equal the
-    number of pairs the oracle's mask (Algorithm 4 and the fraction forms) actually refreshes."""
+    """moe_policy_refreshed_pairs (the C entry point that sizes the FFN launch from the policy alone,
+    without a GPU): the count must equal the number of pairs the oracle's mask (Algorithm 4 and the
+    fraction forms) actually refreshes; shared-expert slots add one pair per token in every step."""
     import numpy as np
     from oracle import moe_oracle as O
 
     rng = np.random.default_rng(7)
     for T, k in ((1, 1), (5, 2), (64, 2), (33, 3)):
+        ctx = B.Context(T_max=T, d=64, F=256, E=4, k=k, dtype="f32")
+        ctx_shared = B.Context(T_max=T, d=64, F=256, E=4, k=k, dtype="f32", n_shared=2)
         s = rng.random((T, k))
         s = -np.sort(-s, axis=1)            # slot 0 carries the largest score, as the router emits them
         cases = [B.Policy(B.REFRESH_ALL), B.Policy(B.REFRESH_NONE)]
@@ -171,5 +174,18 @@ def test_policy_row_count_matches_the_oracle_mask():
         for pol in cases:
             mask, R = O.refresh_mask(s, pol.kind, pol.step_t, pol.stride_n, pol.n_units)
             assert R == int(mask.sum())
-            assert pol.refreshed_pairs(T, k) == R, (T, k, pol)
-            assert pol.refreshed_pairs(T, k, 2) == R + 2 * T      # shared slots: every token, every step
+            assert ctx.moe_policy_refreshed_pairs(pol, T) == (R, R), (T, k, pol)
+            assert ctx_shared.moe_policy_refreshed_pairs(pol, T) == (R + 2 * T, R)    # shared slots: every token, every step
+
+
+def test_policy_row_count_rejects_bad_policies():
+    ctx = B.Context(T_max=16, d=64, F=256, E=4, k=2, dtype="f32")
+    for pol, T in ((B.Policy(B.REFRESH_ALG4, step_t=1, stride_n=0), 8), (B.Policy(B.REFRESH_ALG4, step_t=-1, stride_n=2), 8),
+                   (B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=9), 8), (B.Policy(B.REFRESH_FRACTION_PAIR, n_units=17), 8),
+                   (B.Policy(99), 8)):
+        with pytest.raises(B.MoeError) as e:
+            ctx.moe_policy_refreshed_pairs(pol, T)
+        assert e.value.status == B.MOE_ERR_POLICY
+    with pytest.raises(B.MoeError) as e:
+        ctx.moe_policy_refreshed_pairs(B.Policy(B.REFRESH_ALL), 17)      # T beyond T_max
+    assert e.value.status == B.MOE_ERR_SHAPE

@@ -583,7 +583,7 @@ def test_shared_experts_stay_fresh_under_conditional_refresh():
             m_gpu = G.to_np(g.buf.mask)
             np.testing.assert_array_equal(m_gpu[:, :k], m_from_gpu_scores, err_msg=str(pol))
             np.testing.assert_array_equal(m_gpu[:, k:], 1)
-            assert int(g.buf.n_refresh.item()) == R + n_shared * T == pol.refreshed_pairs(T, k, n_shared)
+            assert int(g.buf.n_refresh.item()) == R + n_shared * T == g.ctx.moe_policy_refreshed_pairs(pol, T)[0]
             if np.array_equal(m_gpu[:, :k], r1.mask):
                 check_shared_tables(g, r1, E, n_shared, with_mask=True)
                 G.assert_close_storage(y1, r1.y, dtype, f"step1 y {pol}", wide_range=True)

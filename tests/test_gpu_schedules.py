@@ -150,7 +150,7 @@ def test_commit_writes_the_rows_of_the_packed_call_into_the_pair_buffer(cfg, T, 
                 B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=Tn // 3)):
         ctx.moe_conditional_refresh(buf.scores, buf.expert_idx, pol, buf.mask, buf.n_refresh, buf.workspace)
         ctx.moe_dispatch(x, buf.expert_idx, buf.mask, None, buf.counts, buf.offsets, buf.perm, buf.inv, buf.workspace)
-        rows = pol.refreshed_pairs(Tn, k)
+        rows = ctx.moe_policy_refreshed_pairs(pol, Tn)[0]
         ctx.moe_expert_ffn_rows(x, buf.perm, buf.offsets, buf.seg_expert, rows, W1, None, W2, None, buf.h_packed,
                                 buf.workspace)
         H = torch.full((Tn, k, d), 3.0, dtype=ctx.torch_dtype, device=G.DEV)
