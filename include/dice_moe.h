@@ -18,7 +18,8 @@
  *
  * Conventions for every entry point
  *   - Returns MOE_OK (0) or a negative moe_status.  Never throws, aborts, allocates device
- *     memory or synchronises the host.  All work is enqueued on `stream` (a hipStream_t passed
+ *     memory or synchronises the host (moe_expert_ffn_status excepted: it waits for the stream).
+ *     A context is used by one host thread at a time.  All work is enqueued on `stream` (a hipStream_t passed
  *     as void*; NULL = the default stream) of the current device.
  *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte aligned, row-major
  *     and contiguous.  moe_shape / moe_policy pointers are HOST pointers read during the call.
@@ -108,9 +109,9 @@ int moe_create(moe_ctx** out, const moe_shape* shape);
 int moe_destroy(moe_ctx* ctx);
 
 /* Bytes of device workspace that moe_conditional_refresh, moe_dispatch and moe_expert_ffn may
- * use for T_max tokens: the FFN's hidden activations [T_max*k, F], and (MOE_BF16) 28 MB of float
+ * use for T_max tokens: the FFN's hidden activations [T_max*k, F], (MOE_BF16) 28 MB of float
  * partial sums for the second GEMM when its reduction is split over several workgroups (few
- * rows).  One workspace can serve all three calls of a layer, and all layers, on one stream. */
+ * rows), and the status words of moe_expert_ffn_status.  One workspace can serve all three calls of a layer, and all layers, on one stream. */
 size_t moe_workspace_bytes(const moe_ctx* ctx);
 
 /* Text of the last error recorded on this context ("" if none); valid until the next call. */
@@ -171,7 +172,11 @@ int moe_policy_refreshed_pairs(moe_ctx* ctx, const moe_policy* policy, int32_t T
  *        sums (offsets[E] = R); perm[T*k]: pair id of packed row r, -1 for r >= R;
  *        inv[T*k]: packed row of pair p, -1 if p is not refreshed.
  * x_packed may be NULL: then only the index outputs are written (x is not read and may be NULL too)
- * and the rows are gathered by the consumer, see moe_expert_ffn_rows. */
+ * and the rows are gathered by the consumer, see moe_expert_ffn_rows.
+ * workspace: moe_workspace_bytes(); at most the first 4 * (E + n_shared) * ceil(T*k / 256) bytes carry
+ * per-workgroup expert counts between the two launches of the sort (they overlap the expert FFN's
+ * hidden activations: calls that share a workspace must run in stream order).  NULL is accepted
+ * when T*k <= 2048 (one workgroup sorts alone). */
 int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const uint8_t* mask,
                  int32_t T, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
                  int32_t* inv, void* workspace, void* stream);
@@ -227,6 +232,15 @@ int moe_expert_ffn_commit(moe_ctx* ctx, const void* x_rows, const int32_t* row_p
                           const void* W1, const float* b1, const void* W2, const float* b2,
                           const float* scores, const uint8_t* mask, int32_t T, void* H_buffer,
                           float* S_buffer, void* workspace, void* stream);
+
+/* Launch check of the expert FFN calls.  Segment sizes live on the device, so the three calls above
+ * size their launch from the host bound max_rows; if the segment table holds more rows than that,
+ * the rows beyond the launched tiles are NOT computed.  Every FFN call records the comparison in
+ * its workspace; this call waits for `stream` (it is the one entry point that synchronises the
+ * host) and reports what the LAST expert FFN call enqueued with this workspace found:
+ * MOE_OK, or MOE_ERR_SHAPE with the two numbers in moe_last_error().  The workspace must have been
+ * used by at least one expert FFN call of this context's shape. */
+int moe_expert_ffn_status(moe_ctx* ctx, const void* workspace, void* stream);
 
 /* Combine + scale + cache blend (Algorithm 1 combine/scale; Algorithm 4 "reuse stale h"):
  *   y_i = sum_{j=0..k-1} s*_ij h*_ij   accumulated in float in slot order,

@@ -27,7 +27,7 @@ MOE_ERR_WORKSPACE, MOE_ERR_CACHE_COLD, MOE_ERR_HIP = -5, -6, -7
 
 EXPORTS = ["moe_create", "moe_destroy", "moe_workspace_bytes", "moe_last_error", "moe_status_string",
            "moe_gate", "moe_policy_refreshed_pairs", "moe_conditional_refresh", "moe_dispatch", "moe_expert_ffn", "moe_expert_ffn_rows",
-           "moe_expert_ffn_commit", "moe_combine", "moe_ep_segments"]
+           "moe_expert_ffn_commit", "moe_expert_ffn_status", "moe_combine", "moe_ep_segments"]
 
 
 class MoeShape(ctypes.Structure):
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
         L.moe_expert_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn_rows.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn_commit.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+        L.moe_expert_ffn_status.argtypes = [vp, vp, vp]
         L.moe_combine.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
         L.moe_ep_segments.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         for name in EXPORTS:
@@ -204,6 +205,11 @@ class Context:
                                                 _ptr(scores, torch.float32), _ptr(mask, torch.uint8), T,
                                                 _ptr(H_buffer, self.torch_dtype), _ptr(S_buffer, torch.float32),
                                                 _ptr(workspace), _stream()))
+
+    def moe_expert_ffn_status(self, workspace):
+        """Waits for the current stream; raises MoeError (MOE_ERR_SHAPE) if the last expert FFN call
+        with this workspace was given a max_rows smaller than its segment table."""
+        self._check(lib().moe_expert_ffn_status(self._h, _ptr(workspace), _stream()))
 
     def moe_combine(self, h_packed, inv, scores, mask, H_cache, S_cache, use_fresh_scores, y):
         T = scores.shape[0]

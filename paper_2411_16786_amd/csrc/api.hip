@@ -11,6 +11,7 @@
 struct moe_ctx {
     moe_shape shape;
     char err[256];
+    uint64_t ffn_ready;     // bit v: the FFN kernels' per-device attributes have been set on device v
 };
 
 namespace {
@@ -40,6 +41,17 @@ size_t hidden_bytes(const moe_ctx* ctx)
 {
     const size_t rows = static_cast<size_t>(ctx->shape.T_max) * slots(ctx);
     return ((rows * ctx->shape.F * elem_bytes(ctx) + 255) / 256) * 256;
+}
+
+// the two status words of the FFN's launch check sit behind the hidden activations and the partial sums
+// (the dispatch scratch shares the start of the workspace with the hidden activations: the calls of one
+// workspace run in stream order)
+size_t status_offset(const moe_ctx* ctx)
+{
+    size_t front = hidden_bytes(ctx);
+    const size_t disp = dicemoe::dispatch_scratch_bytes(static_cast<long long>(ctx->shape.T_max) * slots(ctx), experts(ctx));
+    if (disp > front) front = (disp + 255) / 256 * 256;
+    return front + (is_bf16(ctx) ? dicemoe::kSplitKBytes : 0);
 }
 
 int check_T(moe_ctx* ctx, int32_t T)
@@ -103,6 +115,7 @@ int moe_create(moe_ctx** out, const moe_shape* s)
     ctx->shape = *s;
     ctx->shape.renorm_topk = s->renorm_topk ? 1 : 0;
     ctx->err[0] = '\0';
+    ctx->ffn_ready = 0;
     *out = ctx;
     return MOE_OK;
 }
@@ -117,7 +130,7 @@ int moe_destroy(moe_ctx* ctx)
 size_t moe_workspace_bytes(const moe_ctx* ctx)
 {
     if (!ctx) return 0;
-    return hidden_bytes(ctx) + (is_bf16(ctx) ? dicemoe::kSplitKBytes : 0) + 4096;
+    return status_offset(ctx) + 4096;
 }
 
 const char* moe_last_error(const moe_ctx* ctx) { return ctx ? ctx->err : "null context"; }
@@ -217,15 +230,17 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const u
                  void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv, void* workspace,
                  void* stream)
 {
-    (void)workspace;
     if (!ctx) return MOE_ERR_NULL;
     if (int rc = check_T(ctx, T)) return rc;
     if (!expert_idx || !counts || !offsets || !perm || !inv || (x_packed && !x))
         return fail(ctx, MOE_ERR_NULL, "moe_dispatch: null pointer");
     const moe_shape& s = ctx->shape;
+    // the per-workgroup counts travel from the counting launch to the placing launch at the start of the workspace
+    if (!workspace && dicemoe::dispatch_scratch_bytes(static_cast<long long>(T) * slots(ctx), experts(ctx)) > 0)
+        return fail(ctx, MOE_ERR_WORKSPACE, "moe_dispatch: workspace is null");
     return hip_result(ctx,
                       launch_dispatch(is_bf16(ctx), x, expert_idx, mask, T, s.d, experts(ctx), slots(ctx), x_packed, counts, offsets,
-                                      perm, inv, static_cast<hipStream_t>(stream)),
+                                      perm, inv, static_cast<int32_t*>(workspace), static_cast<hipStream_t>(stream)),
                       "moe_dispatch");
 }
 
@@ -249,11 +264,21 @@ static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, 
         std::snprintf(ctx->err, sizeof(ctx->err), "%s: workspace is null", who);
         return MOE_ERR_WORKSPACE;
     }
+    // per-device kernel attributes, once per context and device (a context serves one host thread at a time)
+    int device = 0;
+    if (hipError_t err = hipGetDevice(&device); err != hipSuccess) return hip_result(ctx, err, who);
+    const bool tracked = device >= 0 && device < 64;
+    if (!tracked || !((ctx->ffn_ready >> device) & 1u)) {
+        if (hipError_t err = dicemoe::prepare_expert_ffn(); err != hipSuccess) return hip_result(ctx, err, who);
+        if (tracked) ctx->ffn_ready |= 1ull << device;
+    }
+    char* ws = static_cast<char*>(workspace);
     return hip_result(ctx,
                       launch_expert_ffn(is_bf16(ctx), x_rows, row_pairs, slots(ctx), seg_offsets, seg_expert, n_segments,
                                         max_rows, s.d, s.F, W1, b1, W2, b2, h_packed, out_pairs, workspace,
-                                        is_bf16(ctx) ? static_cast<char*>(workspace) + hidden_bytes(ctx) : nullptr,
-                                        is_bf16(ctx) ? dicemoe::kSplitKBytes : 0, static_cast<hipStream_t>(stream)),
+                                        is_bf16(ctx) ? ws + status_offset(ctx) - dicemoe::kSplitKBytes : nullptr,
+                                        is_bf16(ctx) ? dicemoe::kSplitKBytes : 0,
+                                        reinterpret_cast<int32_t*>(ws + status_offset(ctx)), static_cast<hipStream_t>(stream)),
                       who);
 }
 
@@ -296,6 +321,22 @@ int moe_expert_ffn_commit(moe_ctx* ctx, const void* x_rows, const int32_t* row_p
                       launch_commit_scores(scores, mask, T, slots(ctx), ctx->shape.k, S_buffer,
                                            static_cast<hipStream_t>(stream)),
                       "moe_expert_ffn_commit");
+}
+
+int moe_expert_ffn_status(moe_ctx* ctx, const void* workspace, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (!workspace) return fail(ctx, MOE_ERR_WORKSPACE, "moe_expert_ffn_status: workspace is null");
+    int32_t words[2] = {0, 0};
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t err = hipMemcpyAsync(words, static_cast<const char*>(workspace) + status_offset(ctx), sizeof(words),
+                                    hipMemcpyDeviceToHost, st);
+    if (err == hipSuccess) err = hipStreamSynchronize(st);
+    if (err != hipSuccess) return hip_result(ctx, err, "moe_expert_ffn_status");
+    if (words[0] != 0)
+        return fail(ctx, MOE_ERR_SHAPE, "expert FFN: the segment table held %ld rows but max_rows was %ld; rows beyond it were not computed",
+                    words[0], words[1]);
+    return MOE_OK;
 }
 
 int moe_combine(moe_ctx* ctx, const void* h_packed, const int32_t* inv, const float* scores, const uint8_t* mask,

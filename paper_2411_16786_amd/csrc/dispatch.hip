@@ -2,14 +2,17 @@
 // (token, slot) pairs by destination expert with a stable counting sort, then gather the token
 // rows into the expert-contiguous buffer.
 //
-// dispatch_index_kernel: one workgroup of 16 wavefronts.  Wave w owns the contiguous range of
-// pair ids [w*L, (w+1)*L), so "wave-major, then lane order" is ascending pair id and the sort is
-// stable by construction.  Lanes that hold the same expert find each other with six ballots (one
-// per bit of the expert id); the lowest such lane keeps a per-wave, per-expert running count in
-// LDS.  Phase A counts (and remembers each pair's rank inside its wave-and-expert group), a scan
-// over (expert, wave) turns the counts into bases, phase B adds base and rank and writes perm / inv
-// (for ranges too long for registers it walks the range again instead).  All integer work, no
-// atomics: the result is unique.
+// Index kernels (count, then place; no workgroup waits for another).  Workgroup b owns the
+// contiguous pair ids [b*256*S, (b+1)*256*S), wave w of it a contiguous quarter, and a wave walks
+// its range in steps of 64, so "workgroup, wave, step, lane" is ascending pair id and the sort is
+// stable by construction.
+//   dispatch_count_kernel: per-workgroup, per-expert counts of refreshed pairs -> scratch[b][e].
+//   dispatch_place_kernel: every workgroup sums the scratch table into the experts' totals and
+//     into the counts of the workgroups before it, scans the totals into the experts' offsets,
+//     ranks its own pairs (lanes that hold the same expert find each other with one ballot per bit
+//     of the expert id; per-wave, per-expert running counts in LDS), and writes perm / inv.
+//     With a single workgroup the table is not needed and the count kernel is not launched.
+// All integer work; the only atomics are integer adds in LDS: the result is unique.
 //
 // dispatch_gather_kernel: one wavefront per token reads the row once (16 bytes per lane per
 // pass) and stores it to each of its refreshed slots' packed rows; bound by HBM traffic
@@ -19,7 +22,7 @@
 
 namespace dicemoe {
 
-constexpr int kIdxThreads = 1024;
+constexpr int kIdxThreads = 256;
 constexpr int kIdxWaves = kIdxThreads / kWave;
 
 // order this wavefront's LDS accesses: reads before the point complete before writes after it
@@ -30,7 +33,7 @@ __device__ __forceinline__ void wave_sync() {
 }
 
 // lanes of this wave that are live and hold the same expert id as the calling lane; nbits = number of
-// bits an expert id can have (ballots are scalar work, and one scalar unit serves the whole workgroup)
+// bits an expert id can have (ballots are scalar work)
 __device__ __forceinline__ uint64_t same_expert_peers(bool live, int e, int nbits) {
     uint64_t peers = __ballot(live);
 #pragma unroll
@@ -44,170 +47,166 @@ __device__ __forceinline__ uint64_t same_expert_peers(bool live, int e, int nbit
     return peers;
 }
 
-constexpr int kChunk = 8;
-
-// Expert ids of one chunk of this wave's pairs, -1 where the pair is past the range, not refreshed
-// or carries a bad id.  The loads are unconditional (index clamped into the range) so that the
-// whole chunk is in flight at once.
-__device__ __forceinline__ void load_chunk(const int32_t* __restrict__ expert_idx, const uint8_t* __restrict__ mask,
-                                           int c0, int lane, int hi, int E, int (&ev)[kChunk]) {
-    uint8_t mv[kChunk];
+// Expert ids of this wave's S steps, -1 where the pair is past the end, not refreshed or carries a
+// bad id.  The loads are unconditional (index clamped) so that all of them are in flight at once.
+template <int S>
+__device__ __forceinline__ void load_steps(const int32_t* __restrict__ expert_idx, const uint8_t* __restrict__ mask,
+                                           int p0, int lane, int N, int E, int (&ev)[S]) {
+    uint8_t mv[S];
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) {
-        const int p = c0 + u * kWave + lane;
-        ev[u] = expert_idx[p < hi ? p : hi - 1];
+    for (int u = 0; u < S; ++u) {
+        const int p = p0 + u * kWave + lane;
+        ev[u] = expert_idx[p < N ? p : N - 1];
     }
     if (mask != nullptr) {
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
-            const int p = c0 + u * kWave + lane;
-            mv[u] = mask[p < hi ? p : hi - 1];
+        for (int u = 0; u < S; ++u) {
+            const int p = p0 + u * kWave + lane;
+            mv[u] = mask[p < N ? p : N - 1];
         }
     } else {
 #pragma unroll
-        for (int u = 0; u < kChunk; ++u) mv[u] = 1;
+        for (int u = 0; u < S; ++u) mv[u] = 1;
     }
 #pragma unroll
-    for (int u = 0; u < kChunk; ++u) {
-        const int p = c0 + u * kWave + lane;
-        const bool ok = p < hi && mv[u] != 0 && static_cast<unsigned>(ev[u]) < static_cast<unsigned>(E);
+    for (int u = 0; u < S; ++u) {
+        const int p = p0 + u * kWave + lane;
+        const bool ok = p < N && mv[u] != 0 && static_cast<unsigned>(ev[u]) < static_cast<unsigned>(E);
         ev[u] = ok ? ev[u] : -1;
     }
 }
 
-// MAXC > 0: the wave's whole range fits in MAXC chunks, so the expert ids and the rank of every pair
-// inside its (wave, expert) group stay in registers between the counting pass and the placement:
-// one pass of loads and ballots instead of two.  MAXC == 0: any N, two passes over global memory.
-template <int MAXC>
-__global__ __launch_bounds__(kIdxThreads) void dispatch_index_kernel(const int32_t* __restrict__ expert_idx,
+template <int S>
+__global__ __launch_bounds__(kIdxThreads) void dispatch_count_kernel(const int32_t* __restrict__ expert_idx,
                                                                     const uint8_t* __restrict__ mask, int N, int E,
+                                                                    int32_t* __restrict__ block_counts)
+{
+    __shared__ int cnt[kMaxExperts];
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const int lane = lane_id();
+    const int nbits = E > 1 ? 32 - __builtin_clz(static_cast<unsigned>(E - 1)) : 0;
+    if (tid < kMaxExperts) cnt[tid] = 0;
+    __syncthreads();
+    const int p0 = (static_cast<int>(blockIdx.x) * kIdxWaves + wave) * kWave * S;
+    if (p0 < N) {                                           // wave-uniform
+        int ev[S];
+        load_steps<S>(expert_idx, mask, p0, lane, N, E, ev);
+#pragma unroll
+        for (int u = 0; u < S; ++u) {
+            const bool live = ev[u] >= 0;
+            const int e = live ? ev[u] : 0;
+            const uint64_t peers = same_expert_peers(live, e, nbits);
+            if (live && (peers & lanemask_lt()) == 0) atomicAdd(&cnt[e], __popcll(peers));   // one add per expert and step
+        }
+    }
+    __syncthreads();
+    if (tid < E) block_counts[static_cast<size_t>(blockIdx.x) * E + tid] = cnt[tid];
+}
+
+template <int S>
+__global__ __launch_bounds__(kIdxThreads) void dispatch_place_kernel(const int32_t* __restrict__ expert_idx,
+                                                                    const uint8_t* __restrict__ mask, int N, int E,
+                                                                    const int32_t* __restrict__ block_counts,
                                                                     int32_t* __restrict__ counts,
                                                                     int32_t* __restrict__ offsets,
                                                                     int32_t* __restrict__ perm,
                                                                     int32_t* __restrict__ inv)
 {
-    __shared__ int wave_run[kIdxWaves][kMaxExperts];  // counts, then running bases
-    __shared__ int s_cnt[kMaxExperts];
+    __shared__ int wave_run[kIdxWaves][kMaxExperts];   // running count of a wave's pairs per expert; at the end its total
+    __shared__ int s_tot[kMaxExperts];                 // pairs per expert over all workgroups
+    __shared__ int s_pre[kMaxExperts];                 // pairs per expert in the workgroups before this one
     __shared__ int s_off[kMaxExperts + 1];
     const int tid = threadIdx.x;
     const int wave = tid / kWave;
     const int lane = lane_id();
+    const int b = blockIdx.x;
+    const int n_blocks = gridDim.x;
     const int nbits = E > 1 ? 32 - __builtin_clz(static_cast<unsigned>(E - 1)) : 0;
-    const int L = (((N + kIdxWaves - 1) / kIdxWaves) + kWave - 1) / kWave * kWave;
-    const int lo = wave * L;
-    const int hi = (lo + L < N) ? lo + L : N;
-
-    wave_run[tid / kMaxExperts][tid % kMaxExperts] = 0;   // 1024 threads cover the 16 x 64 table
+    wave_run[tid / kMaxExperts][tid % kMaxExperts] = 0;   // 256 threads cover the 4 x 64 table
+    if (tid < kMaxExperts) { s_tot[tid] = 0; s_pre[tid] = 0; }
     __syncthreads();
 
-    constexpr int NC = MAXC > 0 ? MAXC : 1;
-    int ev_keep[NC][kChunk];      // expert id, -1 if not live
-    int rank_keep[NC][kChunk];    // pairs of the same wave and expert before this one
-
-    // Both phases walk the range in chunks of kChunk wave-wide steps: all loads of a chunk are
-    // issued first (they are independent), then the steps are processed from registers in order.
-    // phase A: per-wave, per-expert counts of refreshed pairs
-    if (MAXC > 0) {
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int c0 = lo + c * kWave * kChunk;
-            if (c0 < hi) {                                 // wave-uniform
-                load_chunk(expert_idx, mask, c0, lane, hi, E, ev_keep[c]);
-#pragma unroll
-                for (int u = 0; u < kChunk; ++u) {
-                    const bool live = ev_keep[c][u] >= 0;
-                    const int e = live ? ev_keep[c][u] : 0;
-                    const uint64_t peers = same_expert_peers(live, e, nbits);
-                    const int before = __popcll(peers & lanemask_lt());
-                    const int run = wave_run[wave][e];     // every peer reads the same running count ...
-                    rank_keep[c][u] = run + before;
-                    wave_sync();
-                    if (live && before == 0) wave_run[wave][e] = run + __popcll(peers);   // ... then the first updates it
-                    wave_sync();
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < kChunk; ++u) { ev_keep[c][u] = -1; rank_keep[c][u] = 0; }
+    // the table of the other workgroups' counts: totals, and the part that precedes this workgroup
+    if (n_blocks > 1) {
+        for (int i = tid; i < n_blocks * E; i += kIdxThreads) {
+            const int c = block_counts[i];
+            const int bb = i / E, e = i - bb * E;
+            if (c != 0) {
+                atomicAdd(&s_tot[e], c);
+                if (bb < b) atomicAdd(&s_pre[e], c);
             }
+        }
+    }
+
+    // rank of each of this wave's pairs among the wave's pairs of the same expert
+    const int p0 = (b * kIdxWaves + wave) * kWave * S;
+    int ev[S], rank[S];
+    if (p0 < N) {                                           // wave-uniform
+        load_steps<S>(expert_idx, mask, p0, lane, N, E, ev);
+#pragma unroll
+        for (int u = 0; u < S; ++u) {
+            const bool live = ev[u] >= 0;
+            const int e = live ? ev[u] : 0;
+            const uint64_t peers = same_expert_peers(live, e, nbits);
+            const int before = __popcll(peers & lanemask_lt());
+            const int run = wave_run[wave][e];             // every peer reads the same running count ...
+            rank[u] = run + before;
+            wave_sync();
+            if (live && before == 0) wave_run[wave][e] = run + __popcll(peers);   // ... then the first updates it
+            wave_sync();
         }
     } else {
-        for (int c0 = lo; c0 < hi; c0 += kWave * kChunk) {
-            int ev[kChunk];
-            load_chunk(expert_idx, mask, c0, lane, hi, E, ev);
 #pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
-                const bool live = ev[u] >= 0;
-                const int e = live ? ev[u] : 0;
-                const uint64_t peers = same_expert_peers(live, e, nbits);
-                if (live && (peers & lanemask_lt()) == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
-                wave_sync();
-            }
-        }
+        for (int u = 0; u < S; ++u) { ev[u] = -1; rank[u] = 0; }
     }
     __syncthreads();
-
-    // exclusive scan over waves for each expert; then over experts
-    if (tid < E) {
-        int run = 0;
-        for (int w = 0; w < kIdxWaves; ++w) {
-            const int c = wave_run[w][tid];
-            wave_run[w][tid] = run;
-            run += c;
-        }
-        s_cnt[tid] = run;
-        counts[tid] = run;
+    if (n_blocks == 1 && tid < E) {
+        int t = 0;
+#pragma unroll
+        for (int w = 0; w < kIdxWaves; ++w) t += wave_run[w][tid];
+        s_tot[tid] = t;
     }
     __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int e = 0; e < E; ++e) { s_off[e] = run; offsets[e] = run; run += s_cnt[e]; }
-        s_off[E] = run;
-        offsets[E] = run;
+    // exclusive scan over the experts: lane e of the first wave holds expert e's total
+    if (wave == 0) {
+        const int mine = lane < E ? s_tot[lane] : 0;
+        int incl = mine;
+#pragma unroll
+        for (int sh = 1; sh < kWave; sh <<= 1) {
+            const int v = __shfl_up(incl, sh, kWave);
+            if (lane >= sh) incl += v;
+        }
+        if (lane < E) {
+            s_off[lane] = incl - mine;
+            if (b == 0) { counts[lane] = mine; offsets[lane] = incl - mine; }
+        }
+        if (lane == E - 1) {
+            s_off[E] = incl;
+            if (b == 0) offsets[E] = incl;
+        }
     }
     __syncthreads();
     const int R = s_off[E];
 
-    // phase B: final positions
-    if (MAXC > 0) {
+    if (p0 < N) {
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int c0 = lo + c * kWave * kChunk;
-            if (c0 < hi) {
-#pragma unroll
-                for (int u = 0; u < kChunk; ++u) {
-                    const int p = c0 + u * kWave + lane;
-                    const int e = ev_keep[c][u];
-                    int r = -1;
-                    if (e >= 0) {
-                        r = s_off[e] + wave_run[wave][e] + rank_keep[c][u];
-                        perm[r] = p;
-                    }
-                    if (p < hi) inv[p] = r;
-                }
+        for (int u = 0; u < S; ++u) {
+            const int p = p0 + u * kWave + lane;
+            const int e = ev[u];
+            int r = -1;
+            if (e >= 0) {
+                int base = s_off[e] + s_pre[e];
+                for (int w = 0; w < wave; ++w) base += wave_run[w][e];
+                r = base + rank[u];
+                perm[r] = p;
             }
-        }
-    } else {
-        for (int c0 = lo; c0 < hi; c0 += kWave * kChunk) {
-            int ev[kChunk];
-            load_chunk(expert_idx, mask, c0, lane, hi, E, ev);
-#pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
-                const int p = c0 + u * kWave + lane;
-                const bool live = ev[u] >= 0;
-                const int e = live ? ev[u] : 0;
-                const uint64_t peers = same_expert_peers(live, e, nbits);
-                const int before = __popcll(peers & lanemask_lt());
-                int r = -1;
-                if (live) r = s_off[e] + wave_run[wave][e] + before;
-                wave_sync();
-                if (live && before == 0) wave_run[wave][e] = wave_run[wave][e] + __popcll(peers);
-                wave_sync();
-                if (live) perm[r] = p;
-                if (p < hi) inv[p] = r;
+            if (p < N) {
+                inv[p] = r;
+                if (p >= R) perm[p] = -1;                  // packed rows beyond the refreshed ones
             }
         }
     }
-    for (int r = R + tid; r < N; r += kIdxThreads) perm[r] = -1;
 }
 
 template <typename T>
@@ -234,33 +233,61 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const T* __restric
     }
 }
 
+// Steps per wave and workgroups of the index kernels for N pairs.  Up to 2048 pairs one workgroup
+// sorts alone (one launch); beyond, the fewest steps (1, 2, 4, 8) that keep the grid at 256 workgroups
+// or fewer; beyond 2^19 pairs the grid grows instead.
+static void dispatch_plan(long long N, int& steps, int& blocks)
+{
+    steps = 1;
+    if (N <= 8 * kIdxThreads) {
+        while (static_cast<long long>(kIdxThreads) * steps < N) steps *= 2;
+        blocks = 1;
+        return;
+    }
+    while (steps < 8 && (N + static_cast<long long>(kIdxThreads) * steps - 1) / (kIdxThreads * steps) > 256) steps *= 2;
+    const long long b = (N + static_cast<long long>(kIdxThreads) * steps - 1) / (kIdxThreads * steps);
+    blocks = b > 0 ? static_cast<int>(b) : 1;
+}
+
+size_t dispatch_scratch_bytes(long long n_pairs, int E)
+{
+    int steps, blocks;
+    dispatch_plan(n_pairs, steps, blocks);
+    return blocks > 1 ? static_cast<size_t>(blocks) * E * sizeof(int32_t) : 0;
+}
+
+template <int S>
+static void launch_dispatch_index(const int32_t* idx, const uint8_t* mask, int N, int E, int blocks, int32_t* scratch,
+                                  int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv, hipStream_t stream)
+{
+    if (blocks > 1)
+        hipLaunchKernelGGL(dispatch_count_kernel<S>, dim3(blocks), dim3(kIdxThreads), 0, stream, idx, mask, N, E, scratch);
+    hipLaunchKernelGGL(dispatch_place_kernel<S>, dim3(blocks), dim3(kIdxThreads), 0, stream, idx, mask, N, E, scratch,
+                       counts, offsets, perm, inv);
+}
+
 hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const uint8_t* mask, int T_tok, int d,
                            int E, int k, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
-                           int32_t* inv, hipStream_t stream)
+                           int32_t* inv, int32_t* scratch, hipStream_t stream)
 {
     const int N = T_tok * k;
-    // pairs per wave, rounded up to whole wave-wide steps; up to 4 chunks of them stay in registers
-    const int per_wave = (((N + kIdxWaves - 1) / kIdxWaves) + kWave - 1) / kWave * kWave;
-    if (per_wave <= kWave * kChunk)
-        hipLaunchKernelGGL(dispatch_index_kernel<1>, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
-                           offsets, perm, inv);
-    else if (per_wave <= 2 * kWave * kChunk)
-        hipLaunchKernelGGL(dispatch_index_kernel<2>, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
-                           offsets, perm, inv);
-    else if (per_wave <= 4 * kWave * kChunk)
-        hipLaunchKernelGGL(dispatch_index_kernel<4>, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
-                           offsets, perm, inv);
-    else
-        hipLaunchKernelGGL(dispatch_index_kernel<0>, dim3(1), dim3(kIdxThreads), 0, stream, idx, mask, N, E, counts,
-                           offsets, perm, inv);
+    int steps, blocks;
+    dispatch_plan(N, steps, blocks);
+    if (blocks > 1 && scratch == nullptr) return hipErrorInvalidValue;
+    switch (steps) {
+    case 1: launch_dispatch_index<1>(idx, mask, N, E, blocks, scratch, counts, offsets, perm, inv, stream); break;
+    case 2: launch_dispatch_index<2>(idx, mask, N, E, blocks, scratch, counts, offsets, perm, inv, stream); break;
+    case 4: launch_dispatch_index<4>(idx, mask, N, E, blocks, scratch, counts, offsets, perm, inv, stream); break;
+    default: launch_dispatch_index<8>(idx, mask, N, E, blocks, scratch, counts, offsets, perm, inv, stream); break;
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || T_tok == 0 || x_packed == nullptr) return err;   // no packed buffer: index only
-    const int blocks = (T_tok + 3) / 4;
+    const int gblocks = (T_tok + 3) / 4;
     if (bf16)
-        hipLaunchKernelGGL(dispatch_gather_kernel<bf16_t>, dim3(blocks), dim3(256), 0, stream,
+        hipLaunchKernelGGL(dispatch_gather_kernel<bf16_t>, dim3(gblocks), dim3(256), 0, stream,
                            static_cast<const bf16_t*>(x), inv, T_tok, d, k, static_cast<bf16_t*>(x_packed));
     else
-        hipLaunchKernelGGL(dispatch_gather_kernel<float>, dim3(blocks), dim3(256), 0, stream,
+        hipLaunchKernelGGL(dispatch_gather_kernel<float>, dim3(gblocks), dim3(256), 0, stream,
                            static_cast<const float*>(x), inv, T_tok, d, k, static_cast<float*>(x_packed));
     return hipGetLastError();
 }

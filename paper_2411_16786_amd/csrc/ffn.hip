@@ -34,9 +34,11 @@ __global__ __launch_bounds__(256, OCC) void ffn_gemm_bf16_kernel(const bf16_t* _
                                                                  const int32_t* __restrict__ seg_expert, int n_seg,
                                                                  int n_tiles_n, int m_tiles_max,
                                                                  const int32_t* __restrict__ row_index, int row_div,
-                                                                 const int32_t* __restrict__ out_index)
+                                                                 const int32_t* __restrict__ out_index,
+                                                                 int32_t* __restrict__ status, int max_rows)
 {
     constexpr int BK = 64;
+    report_row_overflow(status, seg_offsets, n_seg, max_rows);
     constexpr int CH = BK / 8;          // 16-byte chunks per tile row
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -177,9 +179,11 @@ __global__ __launch_bounds__(256) void ffn_gemm_f32_kernel(const float* __restri
                                                            int N, int K, const int32_t* __restrict__ seg_offsets,
                                                            const int32_t* __restrict__ seg_expert, int n_seg,
                                                            int n_tiles_n, const int32_t* __restrict__ row_index,
-                                                           int row_div, const int32_t* __restrict__ out_index)
+                                                           int row_div, const int32_t* __restrict__ out_index,
+                                                           int32_t* __restrict__ status, int max_rows)
 {
     constexpr int BM = 64, BN = 64, BK = 16;
+    report_row_overflow(status, seg_offsets, n_seg, max_rows);
     __shared__ float As[BK][BM + 4];
     __shared__ float Bs[BK][BN + 4];
     const int tile_m = blockIdx.x / n_tiles_n;
@@ -292,11 +296,24 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     }
 }
 
+// max_rows == 0: no GEMM is launched, but the caller's bound is still checked against the table
+__global__ void row_overflow_check_kernel(int32_t* __restrict__ status, const int32_t* __restrict__ seg_offsets, int n_seg)
+{
+    report_row_overflow(status, seg_offsets, n_seg, 0);
+}
+
+static hipError_t launch_row_overflow_check(int32_t* status, const int32_t* seg_offsets, int n_seg, hipStream_t stream)
+{
+    if (status == nullptr) return hipSuccess;
+    hipLaunchKernelGGL(row_overflow_check_kernel, dim3(1), dim3(64), 0, stream, status, seg_offsets, n_seg);
+    return hipGetLastError();
+}
+
 template <int BM, int BN, int OCC, bool XCD, bool GELU>
 static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                    const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
                                    hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1,
-                                   const int32_t* out_index = nullptr)
+                                   const int32_t* out_index = nullptr, int32_t* status = nullptr)
 {
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
@@ -304,7 +321,7 @@ static hipError_t launch_gemm_bf16(const void* A, const void* W, const float* bi
     hipLaunchKernelGGL((ffn_gemm_bf16_kernel<BM, BN, OCC, XCD, GELU>), dim3(static_cast<unsigned>(bands) * 8 * n_tiles_n),
                        dim3(256), 0, stream, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias,
                        static_cast<bf16_t*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index,
-                       row_div, out_index);
+                       row_div, out_index, status, max_rows);
     return hipGetLastError();
 }
 
@@ -312,14 +329,14 @@ template <bool GELU>
 static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                   const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows,
                                   hipStream_t stream, const int32_t* row_index = nullptr, int row_div = 1,
-                                  const int32_t* out_index = nullptr)
+                                  const int32_t* out_index = nullptr, int32_t* status = nullptr)
 {
     const int n_tiles_n = (N + 63) / 64;
     const int m_tiles = (max_rows + 63) / 64 + n_seg;
     hipLaunchKernelGGL((ffn_gemm_f32_kernel<GELU>), dim3(static_cast<unsigned>(m_tiles) * n_tiles_n), dim3(256), 0,
                        stream, static_cast<const float*>(A), static_cast<const float*>(W), bias,
                        static_cast<float*>(C), N, K, seg_offsets, seg_expert, n_seg, n_tiles_n, row_index, row_div,
-                       out_index);
+                       out_index, status, max_rows);
     return hipGetLastError();
 }
 
@@ -344,7 +361,7 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
                                         int row_div = 1, const int32_t* out_index = nullptr, float* partial = nullptr,
-                                        size_t partial_bytes = 0)
+                                        size_t partial_bytes = 0, int32_t* status = nullptr)
 {
     constexpr int kComputeUnits = 256;
     // tiles dealt to the XCDs by expert (one L2 per XCD: an expert's weight slabs are then fetched by one
@@ -371,7 +388,7 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
         if (splits > 1) {
             hipError_t err = launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, nullptr, C, N, K, seg_offsets, seg_expert, n_seg,
                                                                        max_rows, stream, row_index, row_div, nullptr,
-                                                                       by_expert, partial, splits);
+                                                                       by_expert, partial, splits, status);
             if (err != hipSuccess) return err;
             const int blocks = (max_rows + kReduceRows - 1) / kReduceRows + n_seg;
             hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, partial, splits, max_rows, bias,
@@ -381,34 +398,53 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
     }
     if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6) {
         if (K >= 256)
-            return launch_gemm_bf16_wide<2, 3, 2, 2, 3, GELU, 0, 4, 2>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
-        return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
+            return launch_gemm_bf16_wide<2, 3, 2, 2, 3, GELU, 4, 2>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
+        return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
     }
     if (fits_192 && K >= 256 && tiles(128, 192) <= kComputeUnits && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
+        return launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
     if (fits_192 && tiles(128, 192) * 2 >= kComputeUnits)
-        return launch_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert);
+        return launch_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
     return launch_gemm_bf16<128, 128, 3, true, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
-                                                           row_div, out_index);
+                                                           row_div, out_index, status);
+}
+
+// Every instantiation of the wide kernel that launch_gemm_bf16_auto can pick needs its LDS limit
+// raised once per device.
+template <bool GELU>
+static hipError_t configure_gemm_bf16_auto()
+{
+    hipError_t err = configure_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>();
+    if (err == hipSuccess) err = configure_gemm_bf16_wide<2, 3, 2, 2, 3, GELU, 4, 2>();
+    if (err == hipSuccess) err = configure_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>();
+    if (err == hipSuccess) err = configure_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>();
+    return err;
+}
+
+hipError_t prepare_expert_ffn()
+{
+    hipError_t err = configure_gemm_bf16_auto<true>();
+    if (err == hipSuccess) err = configure_gemm_bf16_auto<false>();
+    return err;
 }
 
 hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_index, int row_div,
                              const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
                              int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_packed,
                              const int32_t* out_index, void* hidden, void* partial, size_t partial_bytes,
-                             hipStream_t stream)
+                             int32_t* status, hipStream_t stream)
 {
-    if (max_rows == 0) return hipSuccess;
+    if (max_rows == 0) return launch_row_overflow_check(status, seg_offsets, n_seg, stream);
     hipError_t err;
     if (bf16) {
         err = launch_gemm_bf16_auto<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream,
-                                          row_index, row_div);
+                                          row_index, row_div, nullptr, nullptr, 0, status);
         if (err != hipSuccess) return err;
         return launch_gemm_bf16_auto<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream,
                                             nullptr, 1, out_index, static_cast<float*>(partial), partial_bytes);
     }
     err = launch_gemm_f32<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
-                                row_div);
+                                row_div, nullptr, status);
     if (err != hipSuccess) return err;
     return launch_gemm_f32<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream, nullptr, 1,
                                   out_index);

@@ -59,6 +59,20 @@ __device__ __forceinline__ void block_barrier() {
     asm volatile("" ::: "memory");
 }
 
+// Launch check on behalf of the caller: the grid of a grouped GEMM is sized from the host's bound
+// max_rows, so a segment table that holds more rows than that leaves tiles uncomputed.  The first
+// thread of the first workgroup records it: status[0] = rows in the table if they exceed the bound,
+// else 0; status[1] = the bound.
+__device__ __forceinline__ void report_row_overflow(int32_t* __restrict__ status, const int32_t* __restrict__ seg_offsets,
+                                                    int n_seg, int max_rows)
+{
+    if (status != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        const int total = seg_offsets[n_seg];
+        status[0] = total > max_rows ? total : 0;
+        status[1] = max_rows;
+    }
+}
+
 // Walk the segment table: which segment and which rows does row tile `tile` cover?
 __device__ __forceinline__ bool find_row_tile(const int32_t* __restrict__ seg_offsets, int n_seg, int BM, int tile,
                                               int& seg, int& row0, int& row_end)

@@ -24,19 +24,28 @@ __device__ __forceinline__ void wait_lgkmcnt() {
 
 #define DICEMOE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Build-time timing aid (off in the library build): bit 0 drops the epilogue, bit 1 the stage loads,
+// bit 2 the fragment reads, bit 3 everything after the tile lookup.  Results are wrong with any bit set.
+#ifndef DICEMOE_FFN_DIAG
+#define DICEMOE_FFN_DIAG 0
+#endif
+
 // workgroups per compute unit that the LDS footprint allows (the register budget follows from it)
 constexpr int wide_occupancy(int tm, int tn, int ast, int wst, int wgm, int wgn) {
     return (ast * tm * wgm + wst * tn * wgn) * 32 * 128 <= 80 * 1024 ? 2 : 1;
 }
 
-template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG, int WGM, int WGN>
+template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WGM, WGN)) void ffn_gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const float* __restrict__ bias,
     bf16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ seg_offsets,
     const int32_t* __restrict__ seg_expert, int n_seg, int n_tiles_n, int m_tiles_max,
     const int32_t* __restrict__ row_index, int row_div, const int32_t* __restrict__ out_index, int by_expert,
-    float* __restrict__ partial, int partial_rows)
+    float* __restrict__ partial, int partial_rows, int32_t* __restrict__ status)
 {
+#if DICEMOE_FFN_DIAG
+    constexpr int DIAG = DICEMOE_FFN_DIAG;
+#endif
     constexpr int NW = WGM * WGN;                  // wavefronts, WGM along the rows by WGN along the columns
     constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
     constexpr int WM = 32 * TM, WN = 32 * TN;
@@ -58,6 +67,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     char* const a_lds = smem;
     char* const w_lds = smem + AST * ABYTES;
 
+    // launch check for the caller: did the segment table hold more rows than the grid was sized for?
+    report_row_overflow(status, seg_offsets, n_seg, partial_rows);
     // ---- which tile (bands of GROUP_M row tiles, XCD x takes the x-th eighth of the sequence)
     int seg, row0, row_end, tile_n, e = -1;
     if (by_expert) {
@@ -76,10 +87,12 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
         if (tile_n >= n_tiles_n) return;
         if (!find_row_tile(seg_offsets, n_seg, BM, tile_m, seg, row0, row_end)) return;
     }
+#if DICEMOE_FFN_DIAG
     if (DIAG & 8) {                                 // timing aid: the tile lookup alone
         if (seg + row0 + row_end + tile_n == -12345) C[0] = 1;
         return;
     }
+#endif
     if (!by_expert) e = seg_expert[seg];
     const int n0 = tile_n * BN;
 
@@ -127,7 +140,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     };
     // load i of a stage: i < QA belongs to the A operand (ring slot sa), the others to W (ring slot sw)
     auto dma = [&](int i, int sa, int sw, const char* a_k, const char* w_k) {
+#if DICEMOE_FFN_DIAG
         if (DIAG & 2) return;
+#endif
         uint32_t off = goff[i];
         asm volatile("" : "+v"(off));          // keeps the zero extension next to the load (scalar base + 32-bit offset form)
         if (i < QA)
@@ -158,7 +173,9 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
 
     bf16x8_v fr[2][NFRAG];                           // [set][A fragments 0..TM-1, then W fragments]
     auto read_frag = [&](int set, int f, const char* sta, const char* stw, int kk) {
+#if DICEMOE_FFN_DIAG
         if (DIAG & 4) return;
+#endif
         const char* p = f < TM ? sta + a_off[kk] + f * 4096 : stw + b_off[kk] + (f - TM) * 4096;
         const u32x4_v v = *reinterpret_cast<const u32x4_v*>(p);
         fr[set][f] = *reinterpret_cast<const bf16x8_v*>(&v);
@@ -201,6 +218,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     block_barrier();
 #pragma unroll
     for (int f = 0; f < NFRAG; ++f) read_frag(0, f, a_lds, w_lds, 0);
+#if DICEMOE_FFN_DIAG
     if (DIAG & 4) {
 #pragma unroll
         for (int f = 0; f < NFRAG; ++f) {
@@ -208,6 +226,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
             fr[0][f] = fr[1][f] = *reinterpret_cast<const bf16x8_v*>(&v);
         }
     }
+#endif
 
     // One 64-deep step kt; its A stage sits in ring slot sa, its W stage in ring slot sw (the rings may
     // differ in depth: the W operand streams from HBM once and gains most from a third stage, the
@@ -354,6 +373,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     wait_lgkmcnt<0>();
     block_barrier();
     if (!live) return;
+#if DICEMOE_FFN_DIAG
     if (DIAG & 1) {
         float s = 0.f;
 #pragma unroll
@@ -365,6 +385,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
         if (s == 1234.5f) C[0] = 1;
         return;
     }
+#endif
     if (partial) {
         // raw sums of this share: lane (m, h) holds, per 32 x 32 block, columns 8g + 4h .. + 3 of row m
         float* dst = partial + static_cast<size_t>(blockIdx.y) * partial_rows * N;
@@ -400,28 +421,31 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     }
 }
 
-template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int DIAG = 0, int WGM = 2, int WGN = 2>
+// The wide kernels use more dynamic LDS than a launch may ask for by default; the limit is a
+// per-device attribute of each kernel, raised by prepare_expert_ffn() before the first launch on a device.
+template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int WGM = 2, int WGN = 2>
+static hipError_t configure_gemm_bf16_wide()
+{
+    constexpr int smem = (AST * 32 * TM * WGM + WST * 32 * TN * WGN) * 128;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, AST, WST, GELU, WGM, WGN>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+}
+
+template <int TM, int TN, int SPREAD, int AST, int WST, bool GELU, int WGM = 2, int WGN = 2>
 static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const float* bias, void* C, int N, int K,
                                         const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg,
                                         int max_rows, hipStream_t stream, const int32_t* row_index = nullptr,
                                         int row_div = 1, const int32_t* out_index = nullptr, int by_expert = 0,
-                                        float* partial = nullptr, int k_splits = 1)
+                                        float* partial = nullptr, int k_splits = 1, int32_t* status = nullptr)
 {
     constexpr int BM = 32 * TM * WGM, BN = 32 * TN * WGN;
-    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, AST, WST, GELU, DIAG, WGM, WGN>;
+    auto kern = ffn_gemm_bf16_wide_kernel<TM, TN, SPREAD, AST, WST, GELU, WGM, WGN>;
     constexpr int smem = (AST * BM + WST * BN) * 128;
     if (k_splits < 1 || (k_splits > 1 && (!partial || GELU))) return hipErrorInvalidValue;
     const int nk_min = K / 64 / k_splits;                         // steps of the smallest share
     if (WST == 3 && nk_min < 4) return hipErrorInvalidValue;      // the three-deep loops are written for at least four steps
     if (WST == 4 && nk_min < 7) return hipErrorInvalidValue;      // the four-deep loop for at least seven
     if (nk_min < 1) return hipErrorInvalidValue;
-    static bool configured = false;
-    if (!configured) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (err != hipSuccess) return err;
-        configured = true;
-    }
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;
     const int bands = (m_tiles + 7) / 8;
@@ -429,7 +453,7 @@ static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const floa
                        dim3(64 * WGM * WGN), smem, stream,
                        static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(W), bias, static_cast<bf16_t*>(C), N,
                        K, seg_offsets, seg_expert, n_seg, n_tiles_n, m_tiles, row_index, row_div, out_index, by_expert,
-                       k_splits > 1 ? partial : nullptr, max_rows);
+                       k_splits > 1 ? partial : nullptr, max_rows, status);
     return hipGetLastError();
 }
 

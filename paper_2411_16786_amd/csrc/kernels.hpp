@@ -23,9 +23,12 @@ hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int n_sh
                                  bool token_mode, int n_value, uint8_t* mask, int32_t* n_refresh,
                                  hipStream_t stream);
 
+// scratch: dispatch_scratch_bytes(T_tok * k, E) bytes of device memory (per-workgroup expert counts handed
+// from the counting launch to the placing launch); may be null when that size is 0
 hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const uint8_t* mask, int T_tok, int d,
                            int E, int k, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
-                           int32_t* inv, hipStream_t stream);
+                           int32_t* inv, int32_t* scratch, hipStream_t stream);
+size_t dispatch_scratch_bytes(long long n_pairs, int E);
 
 hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, const float* scores,
                           const uint8_t* mask, int T_tok, int d, int k, int k_cached, void* H_cache,
@@ -38,7 +41,11 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_i
                              const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
                              int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_out,
                              const int32_t* out_index, void* hidden, void* partial, size_t partial_bytes,
-                             hipStream_t stream);
+                             int32_t* status, hipStream_t stream);
+// status (two int32 on the device, may be null): written by the first GEMM of every call, see
+// report_row_overflow in ffn_mfma.hpp.
+// Once per device before the first launch_expert_ffn there: raises the dynamic-LDS limit of the wide kernels.
+hipError_t prepare_expert_ffn();
 
 // bytes of float partial sums that the split reduction of the second GEMM may use (beyond `hidden`)
 // (at most about 270 workgroups of 128 x 192 float tiles)

@@ -54,7 +54,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 
-__global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float* __restrict__ scores, int T_tok,
+__global__ __launch_bounds__(kSelThreads) void refresh_select_any_kernel(const float* __restrict__ scores, int T_tok,
                                                                     int kc, int k, int slot, int m, int token_mode,
                                                                     int n_value, uint8_t* __restrict__ mask,
                                                                     int32_t* __restrict__ n_refresh)
@@ -148,6 +148,143 @@ __global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float
     }
 }
 
+// The same selection for up to 16 * 1024 tokens, keys held in registers (KPT per thread, token
+// i = u * 1024 + tid).  A most-significant-digit radix select on (key - smallest key): the digit is the
+// top 11 bits of the span the keys still in play cover, so that the 2048 counters are spread over the
+// keys' real range (router scores share their sign and most of their exponent bits: fixed bit fields
+// would send every key to two or three counters, and LDS atomics on one address serialise).  Round r
+// narrows the span by 2^11; it ends early when every key of the threshold digit is admitted, which is
+// the usual case after the second round.  Ties at the threshold go to the lower token, by a block-wide
+// prefix count in token order.
+constexpr int kSelBins = 2048;
+
+template <int KPT>
+__global__ __launch_bounds__(kSelThreads) void refresh_select_kernel(const float* __restrict__ scores, int T_tok,
+                                                                    int kc, int k, int slot, int m, int token_mode,
+                                                                    int n_value, uint8_t* __restrict__ mask,
+                                                                    int32_t* __restrict__ n_refresh)
+{
+    __shared__ uint32_t hist[kSelBins];
+    __shared__ uint32_t wave_a[kSelWaves], wave_b[kSelWaves];
+    __shared__ uint32_t s_bin, s_above, s_cnt;
+    const int tid = threadIdx.x;
+    const int wave = tid / kWave;
+    const int lane = lane_id();
+    if (tid == 0) *n_refresh = n_value;
+
+    uint32_t key[KPT];
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+        const int i = u * kSelThreads + tid;
+        key[u] = order_key(scores[static_cast<size_t>(i < T_tok ? i : T_tok - 1) * kc + slot]);
+    }
+    const bool need_select = (m > 0 && m < T_tok);
+    uint32_t lo = 0, thr = 0;
+    int admit_equal = 0;          // > 0: keys equal to thr are admitted in token order, this many of them
+    bool ties = false;
+    if (need_select) {
+        // smallest and largest key
+        uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+#pragma unroll
+        for (int u = 0; u < KPT; ++u)
+            if (u * kSelThreads + tid < T_tok) { kmin = key[u] < kmin ? key[u] : kmin; kmax = key[u] > kmax ? key[u] : kmax; }
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) {
+            const uint32_t a = __shfl_xor(kmin, sh, kWave), b = __shfl_xor(kmax, sh, kWave);
+            kmin = a < kmin ? a : kmin;
+            kmax = b > kmax ? b : kmax;
+        }
+        if (lane == 0) { wave_a[wave] = kmin; wave_b[wave] = kmax; }
+        __syncthreads();
+        kmin = wave_a[lane & (kSelWaves - 1)];
+        kmax = wave_b[lane & (kSelWaves - 1)];
+#pragma unroll
+        for (int sh = kSelWaves / 2; sh >= 1; sh >>= 1) {
+            const uint32_t a = __shfl_xor(kmin, sh, kWave), b = __shfl_xor(kmax, sh, kWave);
+            kmin = a < kmin ? a : kmin;
+            kmax = b > kmax ? b : kmax;
+        }
+        lo = kmin;
+        uint32_t span = kmax - kmin;              // keys in play lie in [lo, lo + span]
+        uint32_t remaining = static_cast<uint32_t>(m);
+        for (;;) {
+            const int shift = span >= kSelBins ? (32 - __builtin_clz(span)) - 11 : 0;     // span >> shift < 2048
+            __syncthreads();                      // the previous round's reads of hist / s_* are done
+            hist[tid] = 0; hist[tid + kSelThreads] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < KPT; ++u) {
+                const uint32_t rel = key[u] - lo;
+                if (u * kSelThreads + tid < T_tok && key[u] >= lo && rel <= span) atomicAdd(&hist[rel >> shift], 1u);
+            }
+            __syncthreads();
+            // keys in digits above each digit: thread t owns digits 2t and 2t+1; suffix sums over the
+            // threads of a wave by shuffles, over the waves through LDS
+            const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+            uint32_t incl = h0 + h1;              // becomes the sum over lanes >= this one
+#pragma unroll
+            for (int sh = 1; sh < kWave; sh <<= 1) {
+                const uint32_t v = __shfl_down(incl, sh, kWave);
+                if (lane + sh < kWave) incl += v;
+            }
+            if (lane == 0) wave_a[wave] = incl;
+            __syncthreads();
+            uint32_t higher = 0;
+#pragma unroll
+            for (int w = 0; w < kSelWaves; ++w) higher += (w > wave) ? wave_a[w] : 0u;
+            const uint32_t above1 = higher + incl - (h0 + h1);     // keys in digits above 2t+1
+            const uint32_t above0 = above1 + h1;                    // keys in digits above 2t
+            if (above1 < remaining && remaining <= above1 + h1) { s_bin = 2 * tid + 1; s_above = above1; s_cnt = h1; }
+            if (above0 < remaining && remaining <= above0 + h0) { s_bin = 2 * tid; s_above = above0; s_cnt = h0; }
+            __syncthreads();
+            const uint32_t bin = s_bin, cnt = s_cnt;
+            remaining -= s_above;
+            lo += bin << shift;
+            if (remaining == cnt) { thr = lo; break; }              // the whole digit is admitted: keys >= lo
+            if (shift == 0) { thr = lo; ties = true; admit_equal = static_cast<int>(remaining); break; }
+            span = (1u << shift) - 1u;
+        }
+    }
+
+    int running = 0;
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+        const int i = u * kSelThreads + tid;
+        const bool valid = i < T_tok;
+        bool sel;
+        if (!need_select) {
+            sel = (m > 0);
+        } else if (!ties) {
+            sel = key[u] >= thr;
+        } else {
+            const bool eq = valid && key[u] == thr;
+            const uint64_t b = __ballot(eq);
+            __syncthreads();
+            if (lane == 0) wave_a[wave] = __popcll(b);
+            __syncthreads();
+            int before = running + __popcll(b & lanemask_lt());
+            int total = 0;
+#pragma unroll
+            for (int w = 0; w < kSelWaves; ++w) {
+                const int c = static_cast<int>(wave_a[w]);
+                if (w < wave) before += c;
+                total += c;
+            }
+            running += total;
+            sel = key[u] > thr || (eq && before < admit_equal);
+        }
+        if (valid) {
+            for (int j = 0; j < kc; ++j) {
+                uint8_t v;
+                if (j >= k) v = 1;                                   // shared expert: fresh in every step
+                else if (token_mode) v = sel ? 1 : 0;
+                else v = (j < slot) ? 1 : (j == slot ? (sel ? 1 : 0) : 0);
+                mask[static_cast<size_t>(i) * kc + j] = v;
+            }
+        }
+    }
+}
+
 hipError_t launch_refresh_simple(int kind, int T_tok, int k, int n_shared, int off_step, uint32_t seed, int n_value,
                                  uint8_t* mask, int32_t* n_refresh, hipStream_t stream)
 {
@@ -163,8 +300,19 @@ hipError_t launch_refresh_select(const float* scores, int T_tok, int k, int n_sh
                                  bool token_mode, int n_value, uint8_t* mask, int32_t* n_refresh,
                                  hipStream_t stream)
 {
-    hipLaunchKernelGGL(refresh_select_kernel, dim3(1), dim3(kSelThreads), 0, stream, scores, T_tok, k + n_shared, k,
-                       slot, m, token_mode ? 1 : 0, n_value, mask, n_refresh);
+    const int kc = k + n_shared, tm = token_mode ? 1 : 0;
+#define DICEMOE_SELECT(KPT_)                                                                                        \
+    hipLaunchKernelGGL(refresh_select_kernel<KPT_>, dim3(1), dim3(kSelThreads), 0, stream, scores, T_tok, kc, k, slot, \
+                       m, tm, n_value, mask, n_refresh)
+    if (T_tok < 1 || T_tok > 16 * kSelThreads)      // any size: keys re-read from memory in every round
+        hipLaunchKernelGGL(refresh_select_any_kernel, dim3(1), dim3(kSelThreads), 0, stream, scores, T_tok, kc, k,
+                           slot, m, tm, n_value, mask, n_refresh);
+    else if (T_tok <= kSelThreads) DICEMOE_SELECT(1);
+    else if (T_tok <= 2 * kSelThreads) DICEMOE_SELECT(2);
+    else if (T_tok <= 4 * kSelThreads) DICEMOE_SELECT(4);
+    else if (T_tok <= 8 * kSelThreads) DICEMOE_SELECT(8);
+    else DICEMOE_SELECT(16);
+#undef DICEMOE_SELECT
     return hipGetLastError();
 }
 
