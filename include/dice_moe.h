@@ -181,6 +181,19 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const u
                  int32_t T, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
                  int32_t* inv, void* workspace, void* stream);
 
+/* moe_dispatch for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The per-workgroup counts that moe_dispatch
+ * keeps in the caller's workspace live here in a 64 KiB array inside the library's device code (one
+ * per GPU, held until the process ends); the call allocates nothing and returns the same outputs,
+ * bit for bit.  Limit: 4 * (E + n_shared) * ceil(T*k / 256) <= 65536 bytes (e.g. E = 8: up to 2^19
+ * pairs); beyond it the call returns MOE_ERR_SHAPE and launches nothing.  Every call on a GPU shares
+ * that GPU's array: calls that overlap on one GPU (two streams, two threads) race; calls in stream
+ * order are safe, and nothing in the array has to be cleared between them (the counting launch writes
+ * every entry the placing launch reads). */
+int moe_dispatch_noalloc(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const uint8_t* mask,
+                         int32_t T, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
+                         int32_t* inv, void* stream);
+
 /* Grouped expert FFN (Algorithm 1, "x_e <- expert(x_d)"; experts are feed-forward networks):
  * for every segment g, rows seg_offsets[g] .. seg_offsets[g+1]-1 of x_packed go through expert
  * seg_expert[g]:  h = W2_e . gelu(W1_e . x + b1_e) + b2_e,  gelu(u) = u/2 (1 + erf(u/sqrt 2)).

@@ -26,7 +26,7 @@ MOE_ERR_NULL, MOE_ERR_SHAPE, MOE_ERR_DTYPE, MOE_ERR_POLICY = -1, -2, -3, -4
 MOE_ERR_WORKSPACE, MOE_ERR_CACHE_COLD, MOE_ERR_HIP = -5, -6, -7
 
 EXPORTS = ["moe_create", "moe_destroy", "moe_workspace_bytes", "moe_last_error", "moe_status_string",
-           "moe_gate", "moe_policy_refreshed_pairs", "moe_conditional_refresh", "moe_dispatch", "moe_expert_ffn", "moe_expert_ffn_rows",
+           "moe_gate", "moe_policy_refreshed_pairs", "moe_conditional_refresh", "moe_dispatch", "moe_dispatch_noalloc", "moe_expert_ffn", "moe_expert_ffn_rows",
            "moe_expert_ffn_commit", "moe_expert_ffn_status", "moe_combine", "moe_ep_segments"]
 
 
@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
                                                  ctypes.POINTER(i32)]
         L.moe_conditional_refresh.argtypes = [vp, vp, vp, i32, ctypes.POINTER(MoePolicy), vp, vp, vp, vp]
         L.moe_dispatch.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.moe_dispatch_noalloc.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn_rows.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn_commit.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
@@ -175,6 +176,13 @@ class Context:
                                        _ptr(counts, torch.int32), _ptr(offsets, torch.int32),
                                        _ptr(perm, torch.int32), _ptr(inv, torch.int32), _ptr(workspace),
                                        _stream()))
+
+    def moe_dispatch_noalloc(self, x, expert_idx, mask, x_packed, counts, offsets, perm, inv):
+        T = expert_idx.shape[0]
+        self._check(lib().moe_dispatch_noalloc(self._h, _ptr(x, self.torch_dtype), _ptr(expert_idx, torch.int32),
+                                               _ptr(mask, torch.uint8), T, _ptr(x_packed, self.torch_dtype),
+                                               _ptr(counts, torch.int32), _ptr(offsets, torch.int32),
+                                               _ptr(perm, torch.int32), _ptr(inv, torch.int32), _stream()))
 
     def moe_expert_ffn(self, x_packed, seg_offsets, seg_expert, max_rows, W1, b1, W2, b2, h_packed, workspace):
         n_seg = seg_expert.shape[0]

@@ -244,6 +244,27 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const u
                       "moe_dispatch");
 }
 
+int moe_dispatch_noalloc(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const uint8_t* mask, int32_t T,
+                         void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv, void* stream)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    if (int rc = check_T(ctx, T)) return rc;
+    if (!expert_idx || !counts || !offsets || !perm || !inv || (x_packed && !x))
+        return fail(ctx, MOE_ERR_NULL, "moe_dispatch_noalloc: null pointer");
+    const moe_shape& s = ctx->shape;
+    const size_t need = dicemoe::dispatch_scratch_bytes(static_cast<long long>(T) * slots(ctx), experts(ctx));
+    if (need > dicemoe::dispatch_static_scratch_bytes())
+        return fail(ctx, MOE_ERR_SHAPE, "moe_dispatch_noalloc: this T needs %ld bytes of scratch, the library's static buffer holds %ld",
+                    static_cast<long>(need), static_cast<long>(dicemoe::dispatch_static_scratch_bytes()));
+    int32_t* scratch_ptr = nullptr;
+    if (hipError_t err = dicemoe::dispatch_static_scratch(&scratch_ptr); err != hipSuccess)
+        return hip_result(ctx, err, "moe_dispatch_noalloc");
+    return hip_result(ctx,
+                      launch_dispatch(is_bf16(ctx), x, expert_idx, mask, T, s.d, experts(ctx), slots(ctx), x_packed, counts, offsets,
+                                      perm, inv, scratch_ptr, static_cast<hipStream_t>(stream)),
+                      "moe_dispatch_noalloc");
+}
+
 }  // extern "C"
 
 static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, const int32_t* row_pairs,

@@ -17,6 +17,8 @@
 // dispatch_gather_kernel: one wavefront per token reads the row once (16 bytes per lane per
 // pass) and stores it to each of its refreshed slots' packed rows; bound by HBM traffic
 // T*d*b read + R*d*b written.
+#include <mutex>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -290,6 +292,36 @@ hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const u
         hipLaunchKernelGGL(dispatch_gather_kernel<float>, dim3(gblocks), dim3(256), 0, stream,
                            static_cast<const float*>(x), inv, T_tok, d, k, static_cast<float*>(x_packed));
     return hipGetLastError();
+}
+
+// ---- scratch for callers that cannot hand over a workspace (moe_dispatch_noalloc)
+// One array per device, held until the process ends.  Host code never uses the array's name as an
+// address: the device address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = 64 * 1024;
+static __device__ __align__(256) int32_t scratch[kStaticScratchBytes / sizeof(int32_t)];
+
+constexpr int kMaxDevices = 64;
+static int32_t* g_scratch_ptr[kMaxDevices];        // device address of `scratch` on each device, null until looked up
+static std::mutex g_scratch_lock;
+
+size_t dispatch_static_scratch_bytes() { return kStaticScratchBytes; }
+
+hipError_t dispatch_static_scratch(int32_t** out)
+{
+    int device = -1;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess) return err;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (g_scratch_ptr[device] == nullptr) {
+        void* ptr = nullptr;
+        err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));      // the current device's copy of the array
+        if (err != hipSuccess) return err;
+        if (ptr == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<int32_t*>(ptr);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
 }
 
 __global__ void ep_segments_kernel(const int32_t* __restrict__ recv_counts, int n_seg, int E_loc,

@@ -29,6 +29,10 @@ hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const u
                            int E, int k, void* x_packed, int32_t* counts, int32_t* offsets, int32_t* perm,
                            int32_t* inv, int32_t* scratch, hipStream_t stream);
 size_t dispatch_scratch_bytes(long long n_pairs, int E);
+// The library's own scratch for launch_dispatch: a file-scope device array of dispatch_static_scratch_bytes()
+// bytes; *out receives its address on the current device (looked up once per device).  No allocation.
+size_t dispatch_static_scratch_bytes();
+hipError_t dispatch_static_scratch(int32_t** out);
 
 hipError_t launch_combine(bool bf16, const void* h_packed, const int32_t* inv, const float* scores,
                           const uint8_t* mask, int T_tok, int d, int k, int k_cached, void* H_cache,
