@@ -1,15 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE hot path on one MI355X.
 
-A *step* is one pass of the whole hot path (gate -> conditional-refresh mask -> dispatch ->
-grouped expert FFN -> combine) over the 28 stacked layers of the DiT-MoE-XL-shaped workload
-(T = 4096 tokens, d = 1152, E = 8, top-2, F = 4608, bf16), i.e. a full denoising step's MoE work.
-Every layer has its own seeded weights, activations and buffers, all resident in HBM before the
-timed region.  Prints ONE JSON line.
+A *step* is one pass of the whole hot path (gate -> dispatch -> grouped expert FFN -> combine; the
+headline layer is synchronous, i.e. every pair is transmitted and no refresh mask is computed) over
+the 28 stacked layers of the DiT-MoE-XL-shaped workload (T = 4096 tokens, d = 1152, E = 8, top-2,
+F = 4608, bf16), i.e. a full denoising step's MoE work.  Every layer has its own seeded weights,
+activations and buffers, all resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Beside the headline the line carries, measured in the same run:
+  * ``stages``: every stage as its own captured graph over the 28 layers' (cache-cold) buffers, so
+    that launch gaps drop out; the row gather of dispatch is timed as the packed-buffer variant;
+  * ``roofline``: the expert FFN (both grouped GEMMs of one moe_expert_ffn_rows call) against the
+    bf16 MFMA peak, with the split per GEMM from events recorded between the two launches;
+  * ``conditional_refresh``: the 512px Conditional Communication workload (T = 8192, two steps) at
+    refresh fractions 25 / 50 / 75 / 100 %, with its per-stage HBM figures at 50 %;
+  * ``ep_shard``: the grouped FFN over one expert-parallel shard's receive buffer (Zipf load);
+  * ``cpu_baseline``: the oracle on bounded samples of the same workloads on the host cores.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -24,6 +35,15 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
+def kernel_sources_hash():
+    """sha256 over the FFN kernel sources: ties a stored counter summary to the code it was taken on."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2411_16786_amd", "csrc")
+    for name in ("ffn.hip", "ffn_wide.hpp", "ffn_mfma.hpp"):
+        h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -31,15 +51,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--layers", type=int, default=None, help="override the 28 layers (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 256 MiB device copy five times (reference for scaling HBM counters)")
-    ap.add_argument("--refresh-sweep", action="store_true",
-                    help="also time the 512px conditional-communication workload (T=8192) at refresh fractions "
-                         "25/50/75/100 %% and report it under 'conditional_refresh'")
-    ap.add_argument("--ep-shard", action="store_true",
-                    help="also time the grouped FFN over one expert-parallel shard's receive buffer (16384 rows from "
-                         "four source ranks, four local experts under a Zipf load, d=2048, F=8192) and report it under "
-                         "'ep_shard'")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the conditional-refresh sweep and the expert-parallel shard (headline and stages only)")
+    ap.add_argument("--no-calibrate", action="store_true",
+                    help="skip the two machine-ceiling microbenchmarks of the library (plain streaming copy at three "
+                         "sizes; register-resident MFMA loop on random and on zero operands), reported under 'calibration'")
     ap.add_argument("--packed-dispatch", action="store_true",
                     help="materialise x_packed in moe_dispatch instead of gathering rows in the FFN's operand load")
     ap.add_argument("--n-shared", type=int, default=0,
@@ -77,6 +93,9 @@ def main():
     T, d, E, k, F = (args.tokens or c.T), c.d, c.E, c.k, c.F
     n_shared = args.n_shared
     N = T * (k + n_shared)          # (token, slot) pairs: k routed slots and one per shared expert
+    headline = args.workload == "xl" and n_shared == 0 and args.tokens is None and args.schedule == "sync"
+    extras = headline and not args.no_extras
+    b = 2                           # bytes per bf16 element
 
     # ---- inputs: seeded on the host, uploaded once
     t_setup = time.time()
@@ -99,6 +118,29 @@ def main():
             del chunk
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
+
+    def graph_time(fn, reps=5):
+        """Capture ``fn`` (a fixed launch sequence) as one HIP graph and return its mean replay time in ms."""
+        fn()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
 
     deferred = None
     step_no = [0]
@@ -135,7 +177,7 @@ def main():
             L["state"].commit_done = None
             L["buf"] = L["state"].buf                      # where this step's outputs are
 
-    # ---- optional HIP graph of one step (the launch sequence is static)
+    # ---- the headline: K steps, replayed as one HIP graph (the launch sequence is static)
     graph = None
     one_step()
     torch.cuda.synchronize()
@@ -168,97 +210,234 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = T * n_layers * args.steps / elapsed
 
-    # ---- per-stage timing with events on the launch stream (eager, a few passes)
-    stage_names = ["gate", "dispatch", "expert_ffn", "combine"]
-    stage_ms = {s: [] for s in stage_names}
-    n_passes = 3
-    for _ in range(n_passes):
-        for L in layers:
-            buf = L["buf"]
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
-            ev[0].record()
-            ctx.moe_gate(L["x"], L["Wg"], L["bg"], buf.scores, buf.expert_idx)
-            ev[1].record()
-            # as in moe_layer_forward: dispatch writes the index outputs, the FFN gathers the rows itself
-            ctx.moe_dispatch(L["x"], buf.expert_idx, None, None, buf.counts, buf.offsets, buf.perm,
-                             buf.inv, buf.workspace)
-            ev[2].record()
-            ctx.moe_expert_ffn_rows(L["x"], buf.perm, buf.offsets, buf.seg_expert, N, L["W1"], None, L["W2"], None,
-                                    buf.h_packed, buf.workspace)
-            ev[3].record()
-            ctx.moe_combine(buf.h_packed, buf.inv, buf.scores, None, None, None, False, buf.y)
-            ev[4].record()
-            L["ev"] = ev
-        torch.cuda.synchronize()
-        for L in layers:
-            for i, s in enumerate(stage_names):
-                stage_ms[s].append(L["ev"][i].elapsed_time(L["ev"][i + 1]))
-    avg = {s: float(np.mean(v)) for s, v in stage_ms.items()}
-    b = 2
+    # ---- every stage as its own captured graph over all layers (buffers of different layers: cache-cold)
+    def stage_fns():
+        def gate():
+            for L in layers:
+                ctx.moe_gate(L["x"], L["Wg"], L["bg"], L["buf"].scores, L["buf"].expert_idx)
+
+        def dispatch_index():      # as in moe_layer_forward: index outputs only, the FFN gathers the rows itself
+            for L in layers:
+                bf = L["buf"]
+                ctx.moe_dispatch(L["x"], bf.expert_idx, None, None, bf.counts, bf.offsets, bf.perm, bf.inv, bf.workspace)
+
+        def dispatch_packed():     # the expert-parallel send buffer: index kernels + row gather
+            for L in layers:
+                bf = L["buf"]
+                ctx.moe_dispatch(L["x"], bf.expert_idx, None, bf.x_packed, bf.counts, bf.offsets, bf.perm, bf.inv,
+                                 bf.workspace)
+
+        def expert_ffn():
+            for L in layers:
+                bf = L["buf"]
+                ctx.moe_expert_ffn_rows(L["x"], bf.perm, bf.offsets, bf.seg_expert, N, L["W1"], None, L["W2"], None,
+                                        bf.h_packed, bf.workspace)
+
+        def combine():
+            for L in layers:
+                bf = L["buf"]
+                ctx.moe_combine(bf.h_packed, bf.inv, bf.scores, None, None, None, False, bf.y)
+
+        return [("gate", gate), ("dispatch", dispatch_index), ("dispatch_packed", dispatch_packed),
+                ("expert_ffn", expert_ffn), ("combine", combine)]
+
+    for L in layers:                       # the stage graphs run on the layers' own (synchronous) buffers
+        L["buf"] = L.get("state").bufs[0] if "state" in L else L["buf"]
+    avg = {name: graph_time(fn) / n_layers for name, fn in stage_fns()}
+    avg["dispatch_gather"] = max(avg["dispatch_packed"] - avg["dispatch"], 1e-6)
     alg_bytes = {
         "gate": T * d * b + E * d * b + N * 8,
-        "dispatch": 16 * N,          # index outputs only; the row gather rides in the FFN's operand load
+        "dispatch": 16 * N,                                   # index outputs only; the row gather rides in the FFN's operand load
+        "dispatch_packed": T * d * b + N * d * b + 16 * N,    # each token row read once, every pair's row written
+        "dispatch_gather": T * d * b + N * d * b + 4 * N,     # the gather kernel alone (by difference)
         "combine": N * d * b + T * d * b + N * 9,
     }
     ffn_flops = 4.0 * N * d * F
     ffn_tflops = ffn_flops / (avg["expert_ffn"] * 1e-3) / 1e12
-    stages = {s: {"ms": round(avg[s], 5)} for s in stage_names}
+    stages = {s: {"ms": round(v, 5)} for s, v in avg.items()}
     for s, nbytes in alg_bytes.items():
         gbs = nbytes / (avg[s] * 1e-3) / 1e9
         stages[s].update({"algorithmic_bytes": nbytes, "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)})
     stages["expert_ffn"].update({"flops": ffn_flops, "TFLOP/s": round(ffn_tflops, 1),
                                  "frac_mfma": round(ffn_tflops / PEAK_BF16_TFLOPS, 4)})
-    traffic = None
+
+    # ---- the two GEMMs of the FFN call: an event recorded between the launches (eager pass, two rounds)
+    per_kernel = None
+    mids, ends = [], []
+    for rnd in range(2):
+        evs = []
+        for L in layers:
+            bf = L["buf"]
+            e0, em, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            em.record()                                      # creates the handle that the library records again below
+            ctx.moe_expert_ffn_between_event(em)
+            e0.record()
+            ctx.moe_expert_ffn_rows(L["x"], bf.perm, bf.offsets, bf.seg_expert, N, L["W1"], None, L["W2"], None,
+                                    bf.h_packed, bf.workspace)
+            e1.record()
+            evs.append((e0, em, e1))
+        ctx.moe_expert_ffn_between_event(None)
+        torch.cuda.synchronize()
+        if rnd == 1:
+            mids = [e0.elapsed_time(em) for e0, em, _ in evs]
+            ends = [em.elapsed_time(e1) for _, em, e1 in evs]
+    g1_ms, g2_ms = float(np.mean(mids)), float(np.mean(ends))
+    half = ffn_flops / 2
+    per_kernel = {
+        "GEMM1 (W1, bias, GELU; row gather in the operand load)": {
+            "ms": round(g1_ms, 5), "TFLOP/s": round(half / (g1_ms * 1e-3) / 1e12, 1),
+            "frac": round(half / (g1_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+        "GEMM2 (W2, bias)": {
+            "ms": round(g2_ms, 5), "TFLOP/s": round(half / (g2_ms * 1e-3) / 1e12, 1),
+            "frac": round(half / (g2_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+        "note": "events on the launch stream around and between the two launches of each call (eager, launch gaps included)"}
+
+    traffic, traffic_note = None, "no counter summary for these kernel sources"
     tpath = os.path.join(ROOT, "profiles", "bench_xl28_hbm_traffic.txt")
-    if os.path.exists(tpath) and args.workload == "xl" and n_shared == 0:          # rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this same command (not live)
+    if os.path.exists(tpath) and headline:      # rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this same command (not live)
+        stored_hash, stored = None, None
         for line in open(tpath):
             if line.startswith("ffn_traffic_bytes_per_call:"):
-                traffic = int(line.split(":")[1].split()[0])
+                stored = int(line.split(":")[1].split()[0])
+            if line.startswith("kernel_sources_sha256_16:"):
+                stored_hash = line.split(":")[1].strip()
+        if stored is not None and stored_hash == kernel_sources_hash():
+            traffic = stored
+            traffic_note = ("HBM-side bytes per moe_expert_ffn_rows call from profiles/bench_xl28_hbm_traffic.txt "
+                            f"(taken on kernel sources {stored_hash}, the ones that ran here)")
+        elif stored is not None:
+            traffic_note = (f"profiles/bench_xl28_hbm_traffic.txt was taken on kernel sources {stored_hash}, "
+                            f"these are {kernel_sources_hash()}: not reported")
     roofline = {"kernel": "ffn_gemm_bf16_wide_kernel (GEMM1 + GEMM2 of one moe_expert_ffn_rows call)", "bound": "mfma",
                 "achieved": round(ffn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ffn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-                "traffic_note": "HBM-side bytes per moe_expert_ffn_rows call from profiles/bench_xl28_hbm_traffic.txt"}
+                "frac": round(ffn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "traffic_note": traffic_note,
+                "timing": f"mean over {n_layers} calls (one per layer, cold weights) replayed as one HIP graph, HIP events",
+                "per_kernel": per_kernel}
 
-    if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    # ---- machine ceilings from the library's two microbenchmarks
+    calibration = None
+    if not args.no_calibrate:
+        calibration = {"copy": [], "mfma": []}
+        pool_bytes = 512 << 20
+        src = torch.empty(pool_bytes, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
+        for nbytes in (28385280, 75497472, 256 << 20):
+            nrot = pool_bytes // nbytes
+            def copies(nbytes=nbytes, nrot=nrot):
+                for i in range(2 * nrot):
+                    off = (i % nrot) * nbytes
+                    B.moe_calibrate_copy(dst[off:off + nbytes], src[off:off + nbytes], 2048)
+            ms = graph_time(copies) / (2 * nrot)
+            calibration["copy"].append({"bytes_read_plus_written": 2 * nbytes, "us": round(ms * 1e3, 2),
+                                        "GB/s": round(2 * nbytes / (ms * 1e-3) / 1e9, 1)})
         del src, dst
+        sink = torch.zeros(4, dtype=torch.float32, device=dev)
+        iters, wgs = 4096, 256
+        for name, ops in (("random bf16 operands", torch.randn(16 * 256 * 48, device=dev).to(torch.bfloat16)),
+                          ("zero operands", torch.zeros(16 * 256 * 48, dtype=torch.bfloat16, device=dev))):
+            ms = graph_time(lambda ops=ops: [B.moe_calibrate_mfma(ops, sink, iters, wgs) for _ in range(4)]) / 4
+            flops = 2.0 * 32 * 32 * 16 * 8 * iters * 4 * wgs
+            calibration["mfma"].append({"operands": name, "us": round(ms * 1e3, 1),
+                                        "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 1)})
 
-    # ---- optional: Conditional Communication at the 512px shape (two consecutive diffusion steps)
+    # ---- Conditional Communication at the 512px shape (two consecutive diffusion steps), weights of the 28 layers
     cond = None
-    if args.refresh_sweep:
+    cond_cpu = None
+    if extras:
         c4 = WL.CONFIGS[4]
-        li4 = WL.make_layer(4)
-        x_prev, x_next = up(li4.x), up(WL.next_step_x(4, li4.x))
+        assert (c4.d, c4.F, c4.E, c4.k) == (d, F, E, k)
+        n_sets = 8
         ctx4 = B.Context(c4.T, c4.d, c4.F, c4.E, c4.k, "bf16")
-        buf4 = B.LayerBuffers(ctx4, dev, with_cache=True)
-        w4 = (up(li4.Wg), None, up(li4.W1), None, up(li4.W2), None)
+        ws4 = torch.empty(ctx4.workspace_bytes(), dtype=torch.uint8, device=dev)
+        sets = []
+        li4 = None
+        for i in range(n_sets):
+            li = WL.make_layer(4, layer=i, with_experts=False)
+            if i == 0:
+                li4 = li
+            sets.append(dict(x_prev=up(li.x), x_next=up(WL.next_step_x(4, li.x, layer=i)),
+                             buf=B.LayerBuffers(ctx4, dev, with_cache=True, workspace=ws4)))
+        N4 = c4.T * c4.k
+
+        def layer_call(i, pol, which="x_next"):
+            S, L = sets[i % n_sets], layers[i % n_layers]
+            B.moe_layer_forward(ctx4, S["buf"], S[which], L["Wg"], None, L["W1"], None, L["W2"], None, policy=pol)
+
         cond = []
         for frac in (1.0, 0.75, 0.5, 0.25):
             n_units = int(frac * c4.T + 0.5)
             pol = B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=n_units)
-            B.moe_layer_forward(ctx4, buf4, x_prev, *w4, policy=B.Policy(B.REFRESH_ALL))      # fills the cache
-            for _ in range(3):
-                B.moe_layer_forward(ctx4, buf4, x_next, *w4, policy=pol, max_rows=n_units * c4.k)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            reps = 20
-            e0.record()
-            for _ in range(reps):
-                B.moe_layer_forward(ctx4, buf4, x_next, *w4, policy=pol, max_rows=n_units * c4.k)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / reps
-            cond.append({"refresh_fraction": frac, "policy": "FRACTION_TOKEN", "refreshed_pairs": n_units * c4.k,
-                         "ms_per_layer": round(ms, 4), "tokens_per_s": round(c4.T / (ms * 1e-3), 1),
-                         "ffn_flops_needed": 4.0 * n_units * c4.k * c4.d * c4.F})
-        del buf4, w4
+            R = ctx4.moe_policy_refreshed_pairs(pol, c4.T)[0]
+            for i in range(n_sets):                           # step t-1 fills the caches
+                layer_call(i, B.Policy(B.REFRESH_ALL), "x_prev")
+            ms = graph_time(lambda: [layer_call(i, pol) for i in range(n_layers)]) / n_layers
+            entry = {"refresh_fraction": frac, "policy": "FRACTION_TOKEN", "refreshed_pairs": R,
+                     "ms_per_layer": round(ms, 4), "tokens_per_s": round(c4.T / (ms * 1e-3), 1),
+                     "ffn_flops_needed": 4.0 * R * c4.d * c4.F}
+            if frac == 0.5:                                   # the stages of this step on their own (graphs over the sets)
+                def st_refresh():
+                    for i in range(n_layers):
+                        bf = sets[i % n_sets]["buf"]
+                        ctx4.moe_conditional_refresh(bf.scores, bf.expert_idx, pol, bf.mask, bf.n_refresh, bf.workspace)
 
-    # ---- optional: the receive side of an expert-parallel shard (segments ordered [source rank][local expert])
+                def st_dispatch():
+                    for i in range(n_layers):
+                        S = sets[i % n_sets]; bf = S["buf"]
+                        ctx4.moe_dispatch(S["x_next"], bf.expert_idx, bf.mask, None, bf.counts, bf.offsets, bf.perm, bf.inv,
+                                          bf.workspace)
+
+                def st_dispatch_packed():
+                    for i in range(n_layers):
+                        S = sets[i % n_sets]; bf = S["buf"]
+                        ctx4.moe_dispatch(S["x_next"], bf.expert_idx, bf.mask, bf.x_packed, bf.counts, bf.offsets, bf.perm,
+                                          bf.inv, bf.workspace)
+
+                def st_ffn():          # as in moe_layer_forward: the refreshed rows go straight into the cache
+                    for i in range(n_layers):
+                        S, L = sets[i % n_sets], layers[i % n_layers]; bf = S["buf"]
+                        ctx4.moe_expert_ffn_commit(S["x_next"], bf.perm, bf.perm, bf.offsets, bf.seg_expert, R, L["W1"], None,
+                                                   L["W2"], None, None, bf.mask, bf.H_cache, None, bf.workspace, T=c4.T)
+
+                def st_combine():      # every row from the cache, scores written through
+                    for i in range(n_layers):
+                        bf = sets[i % n_sets]["buf"]
+                        ctx4.moe_combine(None, bf.inv, bf.scores, bf.mask, bf.H_cache, bf.S_cache, False, bf.y)
+
+                t = {n_: graph_time(f_) / n_layers for n_, f_ in (("refresh_mask", st_refresh), ("dispatch", st_dispatch),
+                                                                   ("dispatch_packed", st_dispatch_packed),
+                                                                   ("expert_ffn", st_ffn), ("combine", st_combine))}
+                t["dispatch_gather"] = max(t["dispatch_packed"] - t["dispatch"], 1e-6)
+                by = {"dispatch_gather": c4.T * c4.d * b + R * c4.d * b + 4 * N4,
+                      # every pair's row read from the cache (the expert call wrote the fresh ones there), y written
+                      "combine": N4 * c4.d * b + c4.T * c4.d * b + N4 * 9}
+                st = {n_: {"ms": round(v, 5)} for n_, v in t.items()}
+                for n_, nb in by.items():
+                    gbs = nb / (t[n_] * 1e-3) / 1e9
+                    st[n_].update({"algorithmic_bytes": nb, "GB/s": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)})
+                fl = 4.0 * R * c4.d * c4.F
+                st["expert_ffn"].update({"TFLOP/s": round(fl / (t["expert_ffn"] * 1e-3) / 1e12, 1),
+                                         "frac_mfma": round(fl / (t["expert_ffn"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)})
+                entry["stages"] = st
+            cond.append(entry)
+        if not args.no_cpu_baseline:
+            # the oracle on a bounded sample of this workload: two steps of the first 512 tokens, 50 % refreshed
+            from oracle import moe_oracle as O
+            Ts = 512
+            lw = cpu_layers[0]
+            xs0, xs1 = li4.x[:Ts], WL.next_step_x(4, li4.x)[:Ts]
+            H = np.zeros((Ts, c4.k, c4.d)); S_ = np.zeros((Ts, c4.k))
+            O.moe_layer(xs0, lw.Wg, None, lw.W1, None, lw.W2, None, c4.k, policy=O.REFRESH_ALL, H_cache=H, S_cache=S_)
+            t1 = time.perf_counter()
+            O.moe_layer(xs1, lw.Wg, None, lw.W1, None, lw.W2, None, c4.k, policy=O.REFRESH_FRACTION_TOKEN,
+                        n_units=Ts // 2, H_cache=H, S_cache=S_)
+            dt = time.perf_counter() - t1
+            cond_cpu = {"value": round(Ts / dt, 2), "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+                        "sample": f"step t of the first {Ts} tokens at 50 % refresh (FRACTION_TOKEN), {dt:.2f} s"}
+        del sets, ws4
+
+    # ---- the receive side of an expert-parallel shard (segments ordered [source rank][local expert])
     ep_shard = None
-    if args.ep_shard:
+    if extras:
         ep = WL.make_ep_shard()
         c5 = ep.cfg
         rows, W_ranks, E_loc = ep.x_recv.shape[0], ep.recv_counts.shape[0], ep.recv_counts.shape[1]
@@ -267,31 +446,43 @@ def main():
         seg_expert = torch.empty(W_ranks * E_loc, dtype=torch.int32, device=dev)
         ctx5.moe_ep_segments(torch.from_numpy(np.ascontiguousarray(ep.recv_counts, dtype=np.int32)).to(dev),
                              seg_offsets, seg_expert)
-        x5, W1_5, W2_5 = up(ep.x_recv), up(ep.W1), up(ep.W2)
+        n_copies = 4                                              # 268 MB of weights per copy: cold in every call
+        x5 = [up(ep.x_recv) for _ in range(n_copies)]
+        W1_5 = [up(ep.W1) for _ in range(n_copies)]
+        W2_5 = [up(ep.W2) for _ in range(n_copies)]
         h5 = torch.empty((rows, c5.d), dtype=torch.bfloat16, device=dev)
         ws5 = torch.empty(ctx5.workspace_bytes(), dtype=torch.uint8, device=dev)
-        call = lambda: ctx5.moe_expert_ffn(x5, seg_offsets, seg_expert, rows, W1_5, None, W2_5, None, h5, ws5)
-        for _ in range(3):
-            call()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 20
-        e0.record()
-        for _ in range(reps):
-            call()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
+        ms = graph_time(lambda: [ctx5.moe_expert_ffn(x5[i % n_copies], seg_offsets, seg_expert, rows, W1_5[i % n_copies], None,
+                                                     W2_5[i % n_copies], None, h5, ws5) for i in range(2 * n_copies)]) / (2 * n_copies)
+        ctx5.moe_expert_ffn_status(ws5)
         flops5 = 4.0 * rows * c5.d * c5.F
         ep_shard = {"rows": rows, "segments": W_ranks * E_loc, "rows_per_local_expert": ep.recv_counts.sum(axis=0).tolist(),
                     "ms_per_call": round(ms, 4), "rows_per_s": round(rows / (ms * 1e-3), 1), "flops": flops5,
                     "TFLOP/s": round(flops5 / (ms * 1e-3) / 1e12, 1),
                     "frac_mfma": round(flops5 / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        if not args.no_cpu_baseline:
+            from oracle import moe_oracle as O
+            so, se = O.ep_segments(ep.recv_counts)
+            sel = np.random.Generator(np.random.PCG64(5)).choice(rows, size=384, replace=False).astype(np.int32)
+            t1 = time.perf_counter()
+            h_ref = O.expert_ffn(ep.x_recv, so, se, ep.W1, None, ep.W2, None, rows_sel=np.sort(sel))
+            dt = time.perf_counter() - t1
+            got = h5.float().cpu().numpy()[np.sort(sel)]
+            rel = float(np.linalg.norm(got - h_ref) / np.linalg.norm(h_ref))
+            assert rel <= 1e-2, f"expert-parallel shard output differs from the oracle: rel-L2 {rel:.3e}"
+            ep_shard["cpu_baseline"] = {"value": round(len(sel) / dt, 2), "unit": "rows/s", "cores": O.num_threads(),
+                                        "kind": "oracle",
+                                        "sample": f"{len(sel)} sampled rows of the receive buffer, {dt:.2f} s; HIP rows vs "
+                                                  f"the oracle: rel-L2 {rel:.2e}"}
         del x5, W1_5, W2_5, h5, ws5
 
-    # ---- the CPU oracle on a bounded sample of the same workload (layer 0, first tokens)
+    # ---- the CPU oracle on a bounded sample of the headline workload (whole layers)
     cpu_baseline = None
     if not args.no_cpu_baseline:
         from oracle import moe_oracle as O
+        for _ in range(1):
+            run()                                       # the buffers hold the outputs of the timed path again
+        torch.cuda.synchronize()
         t1 = time.perf_counter()
         refs = [O.moe_layer(li.x, li.Wg, li.bg, li.W1, None, li.W2, None, k, n_shared=n_shared) for li in cpu_layers]
         cpu_s = time.perf_counter() - t1
@@ -321,6 +512,8 @@ def main():
                         "cores": O.num_threads(), "kind": "oracle",
                         "sample": f"layers 0..{n_lay - 1} of the same workload, whole layers (T={T}), {cpu_s:.2f} s; "
                                   f"HIP outputs of these layers vs the oracle: worst rel-L2 {worst:.2e}"}
+        if cond_cpu is not None:
+            cpu_baseline["conditional_refresh"] = cond_cpu
 
     out = {
         "metric": "MoE-layer tokens/sec at DiT-MoE-XL shape",
@@ -344,6 +537,10 @@ def main():
         "stages": stages,
         "conditional_refresh": cond,
         "ep_shard": ep_shard,
+        "calibration": calibration,
+        "context": "the paper reports end-to-end DiT-MoE speedups of about 1.2x (1.26x at most) over synchronous expert "
+                   "parallelism on 8 PCIe RTX 4090s, where the two all-to-alls take 62-79 % of a step (Section 3; "
+                   "Experiments); another machine and another metric: context only, no baseline for this line",
         "setup_s": round(setup_s, 1),
     }
     print(json.dumps(out))

@@ -238,7 +238,10 @@ int moe_expert_ffn_rows(moe_ctx* ctx, const void* x, const int32_t* row_pairs,
  *        the other arguments as for moe_expert_ffn
  *   io : H_buffer[T_max*k][d] (dtype), S_buffer[T_max*k] float; rows and scores of pairs that
  *        are not named stay as they are
- * The caller orders this call after the moe_combine that still reads the old buffer contents. */
+ * The caller orders this call after the moe_combine that still reads the old buffer contents.
+ * scores and S_buffer may both be NULL: then only the rows are written (the synchronous layer with a
+ * cache uses this: its moe_combine, called afterwards with h_packed = NULL, reads every row from the
+ * cache and writes the scores through itself, so refreshed rows cross memory once instead of twice). */
 int moe_expert_ffn_commit(moe_ctx* ctx, const void* x_rows, const int32_t* row_pairs,
                           const int32_t* out_pairs, const int32_t* seg_offsets,
                           const int32_t* seg_expert, int32_t n_segments, int32_t max_rows,
@@ -255,13 +258,29 @@ int moe_expert_ffn_commit(moe_ctx* ctx, const void* x_rows, const int32_t* row_p
  * used by at least one expert FFN call of this context's shape. */
 int moe_expert_ffn_status(moe_ctx* ctx, const void* workspace, void* stream);
 
+/* Measurement aids (they compute nothing of the method; the benchmark uses them to print the
+ * per-GEMM split of the expert FFN and the machine ceilings its roofline fractions are read against).
+ * moe_expert_ffn_between_event: from now on every expert FFN call of this context records `event` (a
+ *   hipEvent_t owned by the caller, or NULL to stop) on its stream between its two grouped GEMMs.
+ * moe_calibrate_copy: a plain streaming copy of `bytes` (multiple of 16) device bytes with `workgroups`
+ *   workgroups of 256 lanes, 16 bytes per lane.
+ * moe_calibrate_mfma: a register-resident loop of `iters` x 8 bf16 MFMAs (32x32x16) per wavefront, four
+ *   wavefronts per workgroup, on operand bit patterns read once from `operands` (>= 393216 bytes);
+ *   2 * 32*32*16 * 8 * iters * 4 * workgroups flop; `sink` receives nothing in practice. */
+int moe_expert_ffn_between_event(moe_ctx* ctx, void* event);
+int moe_calibrate_copy(void* dst, const void* src, size_t bytes, int32_t workgroups, void* stream);
+int moe_calibrate_mfma(const void* operands, float* sink, int32_t iters, int32_t workgroups, void* stream);
+
 /* Combine + scale + cache blend (Algorithm 1 combine/scale; Algorithm 4 "reuse stale h"):
  *   y_i = sum_{j=0..k-1} s*_ij h*_ij   accumulated in float in slot order,
  * where a refreshed pair takes h_packed[inv[p]] and scores[p] and writes both through to
  * H_cache[p] / S_cache[p] (when caches are given), and a reused pair takes H_cache[p] and
  * S_cache[p] (or scores[p] if use_fresh_scores).  The cache is keyed by (token, slot): a change of
  * expert_idx[i][j] on a reused pair is not detected, as with a persistent combine buffer.
- *   in : h_packed[R][d], inv[T*k], scores[T][k], mask[T][k] or NULL (= every pair refreshed)
+ *   in : h_packed[R][d], inv[T*k], scores[T][k], mask[T][k] or NULL (= every pair refreshed).
+ *        h_packed may be NULL when caches are given and the shape has no shared experts: the rows of the
+ *        refreshed pairs are then expected in H_cache already (moe_expert_ffn_commit put them there),
+ *        every row is read from H_cache and only the scores are written through
  *   io : H_cache[T][k][d] (dtype) and S_cache[T][k] float, or both NULL when mask is NULL
  *   out: y[T][d] (dtype)
  * A non-NULL mask with a NULL cache returns MOE_ERR_CACHE_COLD; whether a given cache has been

@@ -27,7 +27,8 @@ MOE_ERR_WORKSPACE, MOE_ERR_CACHE_COLD, MOE_ERR_HIP = -5, -6, -7
 
 EXPORTS = ["moe_create", "moe_destroy", "moe_workspace_bytes", "moe_last_error", "moe_status_string",
            "moe_gate", "moe_policy_refreshed_pairs", "moe_conditional_refresh", "moe_dispatch", "moe_dispatch_noalloc", "moe_expert_ffn", "moe_expert_ffn_rows",
-           "moe_expert_ffn_commit", "moe_expert_ffn_status", "moe_combine", "moe_ep_segments"]
+           "moe_expert_ffn_commit", "moe_expert_ffn_status", "moe_expert_ffn_between_event", "moe_calibrate_copy",
+           "moe_calibrate_mfma", "moe_combine", "moe_ep_segments"]
 
 
 class MoeShape(ctypes.Structure):
@@ -76,6 +77,9 @@ def lib() -> ctypes.CDLL:
         L.moe_expert_ffn_rows.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, vp]
         L.moe_expert_ffn_commit.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.moe_expert_ffn_status.argtypes = [vp, vp, vp]
+        L.moe_expert_ffn_between_event.argtypes = [vp, vp]
+        L.moe_calibrate_copy.argtypes = [vp, vp, ctypes.c_size_t, i32, vp]
+        L.moe_calibrate_mfma.argtypes = [vp, vp, i32, i32, vp]
         L.moe_combine.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, vp, vp]
         L.moe_ep_segments.argtypes = [vp, vp, i32, i32, vp, vp, vp]
         for name in EXPORTS:
@@ -202,9 +206,9 @@ class Context:
                                               _ptr(h_packed, self.torch_dtype), _ptr(workspace), _stream()))
 
     def moe_expert_ffn_commit(self, x_rows, row_pairs, out_pairs, seg_offsets, seg_expert, max_rows, W1, b1, W2, b2,
-                              scores, mask, H_buffer, S_buffer, workspace):
+                              scores, mask, H_buffer, S_buffer, workspace, T=None):
         n_seg = seg_expert.shape[0]
-        T = scores.shape[0]
+        T = scores.shape[0] if T is None else T
         self._check(lib().moe_expert_ffn_commit(self._h, _ptr(x_rows, self.torch_dtype), _ptr(row_pairs, torch.int32),
                                                 _ptr(out_pairs, torch.int32), _ptr(seg_offsets, torch.int32),
                                                 _ptr(seg_expert, torch.int32), n_seg, max_rows,
@@ -218,6 +222,10 @@ class Context:
         """Waits for the current stream; raises MoeError (MOE_ERR_SHAPE) if the last expert FFN call
         with this workspace was given a max_rows smaller than its segment table."""
         self._check(lib().moe_expert_ffn_status(self._h, _ptr(workspace), _stream()))
+
+    def moe_expert_ffn_between_event(self, event):
+        """``event``: a recorded-once ``torch.cuda.Event(enable_timing=True)`` (or None to stop)."""
+        self._check(lib().moe_expert_ffn_between_event(self._h, None if event is None else event.cuda_event))
 
     def moe_combine(self, h_packed, inv, scores, mask, H_cache, S_cache, use_fresh_scores, y):
         T = scores.shape[0]
@@ -263,14 +271,18 @@ class LayerBuffers:
 
 
 def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2,
-                      policy: Optional[Policy] = None, max_rows: Optional[int] = None, fuse_gather: bool = True):
+                      policy: Optional[Policy] = None, max_rows: Optional[int] = None, fuse_gather: bool = True,
+                      rows_to_cache: Optional[bool] = None):
     """Enqueue one MoE layer (gate -> refresh -> dispatch -> expert FFN -> combine) on the current
     stream.  With ``policy`` None the layer is synchronous and touches no cache; otherwise the
     mask of ``policy`` is applied and ``buf`` must hold caches.  ``max_rows`` bounds the number of
     refreshed pairs (it sizes the FFN launch and picks its tile shape); by default it is the count
     the policy implies, T*k for the synchronous layer.  With ``fuse_gather`` (default) dispatch
     writes its index outputs only and the FFN reads the token rows through ``perm``; otherwise
-    ``buf.x_packed`` is materialised first (the send buffer of the expert-parallel layout)."""
+    ``buf.x_packed`` is materialised first (the send buffer of the expert-parallel layout).  With
+    ``rows_to_cache`` (default whenever there is a policy, the gather is fused and the shape has no
+    shared experts) the expert call scatters the refreshed rows straight into ``buf.H_cache`` and the
+    combine reads every row from there: same results bit for bit, ``buf.h_packed`` stays unwritten."""
     T = x.shape[0]
     N = T * ctx.slots
     if max_rows is None and policy is not None:
@@ -282,6 +294,18 @@ def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2
                                     buf.workspace)
         mask = buf.mask[:T]
     rows = N if max_rows is None else max_rows
+    if rows_to_cache is None:
+        rows_to_cache = policy is not None and fuse_gather and ctx.n_shared == 0
+    if rows_to_cache:
+        if policy is None or not fuse_gather or ctx.n_shared != 0:
+            raise ValueError("rows_to_cache needs a policy (caches), the fused gather and no shared experts")
+        ctx.moe_dispatch(x, buf.expert_idx[:T], mask, None, buf.counts, buf.offsets, buf.perm, buf.inv,
+                         buf.workspace)
+        ctx.moe_expert_ffn_commit(x, buf.perm, buf.perm, buf.offsets, buf.seg_expert, rows, W1, b1, W2, b2,
+                                  None, mask, buf.H_cache, None, buf.workspace, T=T)
+        ctx.moe_combine(None, buf.inv, buf.scores[:T], mask, buf.H_cache, buf.S_cache,
+                        bool(policy.use_fresh_scores), buf.y[:T])
+        return buf.y[:T]
     if fuse_gather:
         ctx.moe_dispatch(x, buf.expert_idx[:T], mask, None, buf.counts, buf.offsets, buf.perm, buf.inv,
                          buf.workspace)
@@ -297,3 +321,15 @@ def moe_layer_forward(ctx: Context, buf: LayerBuffers, x, Wg, bg, W1, b1, W2, b2
                     buf.H_cache if policy is not None else None,
                     buf.S_cache if policy is not None else None, use_fresh, buf.y[:T])
     return buf.y[:T]
+
+
+def moe_calibrate_copy(dst: torch.Tensor, src: torch.Tensor, workgroups: int):
+    rc = lib().moe_calibrate_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), workgroups, _stream())
+    if rc != MOE_OK:
+        raise MoeError(rc, "moe_calibrate_copy")
+
+
+def moe_calibrate_mfma(operands: torch.Tensor, sink: torch.Tensor, iters: int, workgroups: int):
+    rc = lib().moe_calibrate_mfma(_ptr(operands), _ptr(sink, torch.float32), iters, workgroups, _stream())
+    if rc != MOE_OK:
+        raise MoeError(rc, "moe_calibrate_mfma")

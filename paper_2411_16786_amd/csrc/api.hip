@@ -12,6 +12,7 @@ struct moe_ctx {
     moe_shape shape;
     char err[256];
     uint64_t ffn_ready;     // bit v: the FFN kernels' per-device attributes have been set on device v
+    hipEvent_t ffn_between; // profiling aid: recorded between the two GEMMs of every expert FFN call (or null)
 };
 
 namespace {
@@ -116,6 +117,7 @@ int moe_create(moe_ctx** out, const moe_shape* s)
     ctx->shape.renorm_topk = s->renorm_topk ? 1 : 0;
     ctx->err[0] = '\0';
     ctx->ffn_ready = 0;
+    ctx->ffn_between = nullptr;
     *out = ctx;
     return MOE_OK;
 }
@@ -299,7 +301,8 @@ static int expert_ffn_common(moe_ctx* ctx, const char* who, const void* x_rows, 
                                         max_rows, s.d, s.F, W1, b1, W2, b2, h_packed, out_pairs, workspace,
                                         is_bf16(ctx) ? ws + status_offset(ctx) - dicemoe::kSplitKBytes : nullptr,
                                         is_bf16(ctx) ? dicemoe::kSplitKBytes : 0,
-                                        reinterpret_cast<int32_t*>(ws + status_offset(ctx)), static_cast<hipStream_t>(stream)),
+                                        reinterpret_cast<int32_t*>(ws + status_offset(ctx)), static_cast<hipStream_t>(stream),
+                                        ctx->ffn_between),
                       who);
 }
 
@@ -333,15 +336,37 @@ int moe_expert_ffn_commit(moe_ctx* ctx, const void* x_rows, const int32_t* row_p
 {
     if (!ctx) return MOE_ERR_NULL;
     if (int rc = check_T(ctx, T)) return rc;
-    if (!out_pairs || !scores || !H_buffer || !S_buffer)
+    if (!out_pairs || !H_buffer || ((scores == nullptr) != (S_buffer == nullptr)))
         return fail(ctx, MOE_ERR_NULL, "moe_expert_ffn_commit: null pointer");
     if (int rc = expert_ffn_common(ctx, "moe_expert_ffn_commit", x_rows, row_pairs, seg_offsets, seg_expert, n_segments,
                                    max_rows, W1, b1, W2, b2, H_buffer, out_pairs, workspace, stream))
         return rc;
+    if (!scores) return MOE_OK;              // the scores stay with the caller (moe_combine writes them through)
     return hip_result(ctx,
                       launch_commit_scores(scores, mask, T, slots(ctx), ctx->shape.k, S_buffer,
                                            static_cast<hipStream_t>(stream)),
                       "moe_expert_ffn_commit");
+}
+
+int moe_expert_ffn_between_event(moe_ctx* ctx, void* event)
+{
+    if (!ctx) return MOE_ERR_NULL;
+    ctx->ffn_between = static_cast<hipEvent_t>(event);
+    return MOE_OK;
+}
+
+int moe_calibrate_copy(void* dst, const void* src, size_t bytes, int32_t workgroups, void* stream)
+{
+    if (!dst || !src) return MOE_ERR_NULL;
+    if (bytes % 16 != 0 || workgroups < 1) return MOE_ERR_SHAPE;
+    return dicemoe::launch_calibrate_copy(dst, src, bytes, workgroups, static_cast<hipStream_t>(stream)) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+int moe_calibrate_mfma(const void* operands, float* sink, int32_t iters, int32_t workgroups, void* stream)
+{
+    if (!operands || !sink) return MOE_ERR_NULL;
+    if (iters < 1 || workgroups < 1) return MOE_ERR_SHAPE;
+    return dicemoe::launch_calibrate_mfma(operands, sink, iters, workgroups, static_cast<hipStream_t>(stream)) == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 int moe_expert_ffn_status(moe_ctx* ctx, const void* workspace, void* stream)
@@ -365,7 +390,9 @@ int moe_combine(moe_ctx* ctx, const void* h_packed, const int32_t* inv, const fl
 {
     if (!ctx) return MOE_ERR_NULL;
     if (int rc = check_T(ctx, T)) return rc;
-    if (!h_packed || !inv || !scores || !y) return fail(ctx, MOE_ERR_NULL, "moe_combine: null pointer");
+    if (!inv || !scores || !y) return fail(ctx, MOE_ERR_NULL, "moe_combine: null pointer");
+    if (!h_packed && (!H_cache || ctx->shape.n_shared != 0))
+        return fail(ctx, MOE_ERR_NULL, "moe_combine: h_packed may be null only with a cache and without shared experts");
     if (mask && (!H_cache || !S_cache))
         return fail(ctx, MOE_ERR_CACHE_COLD, "moe_combine: a refresh mask was given without a cache");
     if ((H_cache == nullptr) != (S_cache == nullptr))

@@ -6,7 +6,9 @@
 // One wavefront per token gathers its k rows (fresh rows from the packed buffer through inv,
 // reused rows from the cache), accumulates in float in slot order 0..k-1 (fixed order, no
 // atomics: reproducible), stores y, and writes refreshed rows and scores through to the cache.
-// Bound by HBM traffic: k rows read, one row written, plus the write-through.
+// Bound by HBM traffic: k rows read, one row written, plus the write-through.  Without a packed
+// buffer (h_packed null) the expert call has already scattered the fresh rows into the cache: every
+// row is then read from the cache and only the scores are written through.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -14,8 +16,11 @@ namespace dicemoe {
 
 // KK > 0: k == KK, the per-pair scalars (packed row, score, fresh or reused) are read once per token
 // and the k row loads of a 16-byte column slice are issued together; KK == 0: any k, pair by pair.
+// NP > 0: a row is at most NP passes of 64 lanes x 16 bytes, and the loads of all passes are issued
+// before the first result is formed (one memory round trip per token instead of one per pass: with
+// sixteen wavefronts per compute unit the kernel is bound by latency, not by issue); NP == 0: any d.
 // Slots k_cached..k-1 (shared experts, fresh in every step) are never written to the caches.
-template <typename T, int KK>
+template <typename T, int KK, int NP>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_packed, const int32_t* __restrict__ inv,
                                                       const float* __restrict__ scores,
                                                       const uint8_t* __restrict__ mask, int T_tok, int d, int k,
@@ -42,14 +47,46 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
             const size_t p = p0 + j;
             fresh[j] = (mask == nullptr) || mask[p] != 0;
             if (fresh[j]) {
-                const int r = inv[p];
-                src[j] = r >= 0 ? hp + static_cast<size_t>(r) * nvec : nullptr;
+                if (hp != nullptr) {
+                    const int r = inv[p];
+                    src[j] = r >= 0 ? hp + static_cast<size_t>(r) * nvec : nullptr;
+                } else {
+                    src[j] = hc + p * nvec;            // the expert call has put the fresh row into the cache itself
+                }
                 sc[j] = scores[p];
             } else {
                 src[j] = hc + p * nvec;
                 sc[j] = use_fresh ? scores[p] : S_cache[p];
             }
         }
+        if (NP > 0) {
+            constexpr int NPN = NP > 0 ? NP : 1;
+            u32x4_t v[NPN][KN];
+#pragma unroll
+            for (int p = 0; p < NPN; ++p) {
+                const int c = lane + p * kWave;
+#pragma unroll
+                for (int j = 0; j < KN; ++j) v[p][j] = (src[j] && c < nvec) ? src[j][c] : u32x4_t{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int p = 0; p < NPN; ++p) {
+                const int c = lane + p * kWave;
+                if (c >= nvec) break;
+                float acc[V];
+#pragma unroll
+                for (int t = 0; t < V; ++t) acc[t] = 0.f;
+#pragma unroll
+                for (int j = 0; j < KN; ++j) {
+                    float f[V];
+                    Store<T>::unpack(v[p][j], f);
+#pragma unroll
+                    for (int t = 0; t < V; ++t) acc[t] = fmaf(sc[j], f[t], acc[t]);
+                    if (fresh[j] && hc && hp && j < k_cached) hc[(p0 + j) * nvec + c] = v[p][j];
+                }
+                const uint4 packed = Store<T>::pack(acc);
+                yo[c] = u32x4_t{packed.x, packed.y, packed.z, packed.w};
+            }
+        } else
         for (int c = lane; c < nvec; c += kWave) {
             u32x4_t v[KN];
 #pragma unroll
@@ -63,7 +100,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
                 Store<T>::unpack(v[j], f);
 #pragma unroll
                 for (int t = 0; t < V; ++t) acc[t] = fmaf(sc[j], f[t], acc[t]);
-                if (fresh[j] && hc && j < k_cached) hc[(p0 + j) * nvec + c] = v[j];
+                if (fresh[j] && hc && hp && j < k_cached) hc[(p0 + j) * nvec + c] = v[j];
             }
             const uint4 packed = Store<T>::pack(acc);
             yo[c] = u32x4_t{packed.x, packed.y, packed.z, packed.w};
@@ -79,10 +116,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ h_pa
                 u32x4_t v = u32x4_t{0u, 0u, 0u, 0u};
                 float s;
                 if (is_fresh) {
-                    const int r = inv[p];
-                    if (r >= 0) v = hp[static_cast<size_t>(r) * nvec + c];
+                    if (hp != nullptr) {
+                        const int r = inv[p];
+                        if (r >= 0) v = hp[static_cast<size_t>(r) * nvec + c];
+                        if (hc && j < k_cached) hc[p * nvec + c] = v;
+                    } else {
+                        v = hc[p * nvec + c];
+                    }
                     s = scores[p];
-                    if (hc && j < k_cached) hc[p * nvec + c] = v;
                 } else {
                     v = hc[p * nvec + c];
                     s = use_fresh ? scores[p] : S_cache[p];
@@ -108,15 +149,25 @@ static void launch_combine_t(const void* h_packed, const int32_t* inv, const flo
                              void* y, hipStream_t stream)
 {
     const int blocks = (T_tok + 3) / 4;
-#define DICEMOE_COMBINE(KK_)                                                                                     \
-    hipLaunchKernelGGL((combine_kernel<T, KK_>), dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(h_packed), \
-                       inv, scores, mask, T_tok, d, k, k_cached, static_cast<T*>(H_cache), S_cache, use_fresh,            \
+    const int passes = (d / Store<T>::kVec + kWave - 1) / kWave;
+#define DICEMOE_COMBINE_NP(KK_, NP_)                                                                                  \
+    hipLaunchKernelGGL((combine_kernel<T, KK_, NP_>), dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(h_packed), \
+                       inv, scores, mask, T_tok, d, k, k_cached, static_cast<T*>(H_cache), S_cache, use_fresh,             \
                        static_cast<T*>(y))
+#define DICEMOE_COMBINE(KK_)                                                  \
+    do {                                                                      \
+        if (passes == 1) DICEMOE_COMBINE_NP(KK_, 1);                          \
+        else if (passes == 2) DICEMOE_COMBINE_NP(KK_, 2);                     \
+        else if (passes == 3) DICEMOE_COMBINE_NP(KK_, 3);                     \
+        else if (passes == 4) DICEMOE_COMBINE_NP(KK_, 4);                     \
+        else DICEMOE_COMBINE_NP(KK_, 0);                                      \
+    } while (0)
     if (k == 1) DICEMOE_COMBINE(1);
     else if (k == 2) DICEMOE_COMBINE(2);
     else if (k == 3) DICEMOE_COMBINE(3);
     else if (k == 4) DICEMOE_COMBINE(4);
-    else DICEMOE_COMBINE(0);
+    else DICEMOE_COMBINE_NP(0, 0);
+#undef DICEMOE_COMBINE_NP
 #undef DICEMOE_COMBINE
 }
 

@@ -211,9 +211,11 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_place_kernel(const int32
     }
 }
 
-template <typename T>
+// NP > 0: a row is at most NP passes of 64 lanes x 16 bytes; all passes are loaded before the first
+// store (one memory round trip per token); NP == 0: any row length, pass by pass.
+template <typename T, int NP>
 __global__ __launch_bounds__(256) void dispatch_gather_kernel(const T* __restrict__ x, const int32_t* __restrict__ inv,
-                                                              int T_tok, int d, int k, T* __restrict__ x_packed)
+                                                              int T_tok, int d, int k, int all_pairs, T* __restrict__ x_packed)
 {
     constexpr int V = Store<T>::kVec;
     const int tok = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -221,16 +223,56 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const T* __restric
     const int lane = lane_id();
     const int nvec = d / V;
     const int32_t* rows = inv + static_cast<size_t>(tok) * k;
+    const u32x4_t* src = reinterpret_cast<const u32x4_t*>(x + static_cast<size_t>(tok) * d);
+    u32x4_t* dst = reinterpret_cast<u32x4_t*>(x_packed);
+    if (NP > 0 && all_pairs) {
+        // every pair is refreshed: the row is needed whatever inv says, so its loads go out together with
+        // the loads of the destinations instead of behind them
+        constexpr int NPN = NP > 0 ? NP : 1;
+        u32x4_t v[NPN];
+#pragma unroll
+        for (int p = 0; p < NPN; ++p) {
+            const int c = lane + p * kWave;
+            v[p] = c < nvec ? src[c] : u32x4_t{0u, 0u, 0u, 0u};
+        }
+        for (int j = 0; j < k; ++j) {
+            const int r = rows[j];
+            if (r < 0) continue;
+#pragma unroll
+            for (int p = 0; p < NPN; ++p) {
+                const int c = lane + p * kWave;
+                if (c < nvec) dst[static_cast<size_t>(r) * nvec + c] = v[p];
+            }
+        }
+        return;
+    }
     bool any = false;
     for (int j = 0; j < k; ++j) any |= rows[j] >= 0;
     if (!any) return;
-    const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(tok) * d);
-    uint4* dst = reinterpret_cast<uint4*>(x_packed);
-    for (int c = lane; c < nvec; c += kWave) {
-        const uint4 v = src[c];
+    if (NP > 0) {
+        constexpr int NPN = NP > 0 ? NP : 1;
+        u32x4_t v[NPN];
+#pragma unroll
+        for (int p = 0; p < NPN; ++p) {
+            const int c = lane + p * kWave;
+            v[p] = c < nvec ? src[c] : u32x4_t{0u, 0u, 0u, 0u};
+        }
         for (int j = 0; j < k; ++j) {
             const int r = rows[j];
-            if (r >= 0) dst[static_cast<size_t>(r) * nvec + c] = v;
+            if (r < 0) continue;
+#pragma unroll
+            for (int p = 0; p < NPN; ++p) {
+                const int c = lane + p * kWave;
+                if (c < nvec) dst[static_cast<size_t>(r) * nvec + c] = v[p];
+            }
+        }
+    } else {
+        for (int c = lane; c < nvec; c += kWave) {
+            const u32x4_t v = src[c];
+            for (int j = 0; j < k; ++j) {
+                const int r = rows[j];
+                if (r >= 0) dst[static_cast<size_t>(r) * nvec + c] = v;
+            }
         }
     }
 }
@@ -285,12 +327,23 @@ hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const u
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || T_tok == 0 || x_packed == nullptr) return err;   // no packed buffer: index only
     const int gblocks = (T_tok + 3) / 4;
-    if (bf16)
-        hipLaunchKernelGGL(dispatch_gather_kernel<bf16_t>, dim3(gblocks), dim3(256), 0, stream,
-                           static_cast<const bf16_t*>(x), inv, T_tok, d, k, static_cast<bf16_t*>(x_packed));
-    else
-        hipLaunchKernelGGL(dispatch_gather_kernel<float>, dim3(gblocks), dim3(256), 0, stream,
-                           static_cast<const float*>(x), inv, T_tok, d, k, static_cast<float*>(x_packed));
+    const int passes = (d / (bf16 ? 8 : 4) + kWave - 1) / kWave;
+#define DICEMOE_GATHER(T_, NP_)                                                                                      \
+    hipLaunchKernelGGL((dispatch_gather_kernel<T_, NP_>), dim3(gblocks), dim3(256), 0, stream, static_cast<const T_*>(x), \
+                       inv, T_tok, d, k, mask == nullptr ? 1 : 0, static_cast<T_*>(x_packed))
+    if (bf16) {
+        if (passes == 1) DICEMOE_GATHER(bf16_t, 1);
+        else if (passes == 2) DICEMOE_GATHER(bf16_t, 2);
+        else if (passes == 3) DICEMOE_GATHER(bf16_t, 3);
+        else if (passes == 4) DICEMOE_GATHER(bf16_t, 4);
+        else DICEMOE_GATHER(bf16_t, 0);
+    } else {
+        if (passes == 1) DICEMOE_GATHER(float, 1);
+        else if (passes == 2) DICEMOE_GATHER(float, 2);
+        else if (passes <= 4) DICEMOE_GATHER(float, 4);
+        else DICEMOE_GATHER(float, 0);
+    }
+#undef DICEMOE_GATHER
     return hipGetLastError();
 }
 

@@ -432,7 +432,7 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_i
                              const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
                              int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_packed,
                              const int32_t* out_index, void* hidden, void* partial, size_t partial_bytes,
-                             int32_t* status, hipStream_t stream)
+                             int32_t* status, hipStream_t stream, hipEvent_t between)
 {
     if (max_rows == 0) return launch_row_overflow_check(status, seg_offsets, n_seg, stream);
     hipError_t err;
@@ -440,12 +440,14 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_i
         err = launch_gemm_bf16_auto<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream,
                                           row_index, row_div, nullptr, nullptr, 0, status);
         if (err != hipSuccess) return err;
+        if (between != nullptr && (err = hipEventRecord(between, stream)) != hipSuccess) return err;
         return launch_gemm_bf16_auto<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream,
                                             nullptr, 1, out_index, static_cast<float*>(partial), partial_bytes);
     }
     err = launch_gemm_f32<true>(x_rows, W1, b1, hidden, F, d, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index,
                                 row_div, nullptr, status);
     if (err != hipSuccess) return err;
+    if (between != nullptr && (err = hipEventRecord(between, stream)) != hipSuccess) return err;
     return launch_gemm_f32<false>(hidden, W2, b2, h_packed, d, F, seg_offsets, seg_expert, n_seg, max_rows, stream, nullptr, 1,
                                   out_index);
 }

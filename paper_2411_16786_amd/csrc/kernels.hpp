@@ -45,7 +45,8 @@ hipError_t launch_expert_ffn(bool bf16, const void* x_rows, const int32_t* row_i
                              const int32_t* seg_offsets, const int32_t* seg_expert, int n_seg, int max_rows, int d,
                              int F, const void* W1, const float* b1, const void* W2, const float* b2, void* h_out,
                              const int32_t* out_index, void* hidden, void* partial, size_t partial_bytes,
-                             int32_t* status, hipStream_t stream);
+                             int32_t* status, hipStream_t stream, hipEvent_t between = nullptr);
+// between: if given, recorded on the stream after the first GEMM has been enqueued (per-GEMM timing)
 // status (two int32 on the device, may be null): written by the first GEMM of every call, see
 // report_row_overflow in ffn_mfma.hpp.
 // Once per device before the first launch_expert_ffn there: raises the dynamic-LDS limit of the wide kernels.
@@ -58,6 +59,11 @@ constexpr size_t kSplitKBytes = static_cast<size_t>(288) * 128 * 192 * sizeof(fl
 // S_buffer[p] = scores[p] for the routed slots (j < k_cached) of every pair with mask[p] != 0 (all if mask is null)
 hipError_t launch_commit_scores(const float* scores, const uint8_t* mask, int T_tok, int k, int k_cached,
                                 float* S_buffer, hipStream_t stream);
+
+// measurement aids (calibrate.hip): a plain copy of `bytes` (multiple of 16) and a register-resident MFMA loop
+// (operands: 16 x 256 x 96 bytes of bf16 bit patterns; flops = workgroups * 4 * iters * 8 * 32768)
+hipError_t launch_calibrate_copy(void* dst, const void* src, size_t bytes, int workgroups, hipStream_t stream);
+hipError_t launch_calibrate_mfma(const void* operands, float* sink, int iters, int workgroups, hipStream_t stream);
 
 hipError_t launch_ep_segments(const int32_t* recv_counts, int n_seg, int E_loc, int32_t* seg_offsets,
                               int32_t* seg_expert, hipStream_t stream);

@@ -426,9 +426,9 @@ def test_layer_forward_with_the_gather_folded_into_the_ffn(cfg, T):
         h_sync = G.to_np(buf.h_packed)[:R].copy()
         if fused:
             assert (G.to_np(buf.x_packed) == -5.0).all()        # never materialised
-        B.moe_layer_forward(ctx, buf, x0, *args, policy=B.Policy(B.REFRESH_ALL), fuse_gather=fused)
+        B.moe_layer_forward(ctx, buf, x0, *args, policy=B.Policy(B.REFRESH_ALL), fuse_gather=fused, rows_to_cache=False)
         y_off = B.moe_layer_forward(ctx, buf, x1, *args, policy=B.Policy(B.REFRESH_ALG4, step_t=1, stride_n=2),
-                                    fuse_gather=fused).clone()
+                                    fuse_gather=fused, rows_to_cache=False).clone()
         torch.cuda.synchronize()
         R1 = int(G.to_np(buf.offsets)[-1])
         assert R1 == Tn                                          # slot 0 of every token
@@ -1002,3 +1002,37 @@ def test_expert_ffn_reports_a_max_rows_below_the_segment_table():
         ctx32.moe_expert_ffn_status(ws32)
     ctx32.moe_expert_ffn(x32, so, se, rows, *a32)
     ctx32.moe_expert_ffn_status(ws32)
+
+
+@pytest.mark.parametrize("cfg,T", [(1, None), (2, None), (3, 1500)])
+def test_expert_rows_written_straight_into_the_cache_give_the_same_bits(cfg, T):
+    """The default path of a layer with a cache (Algorithm 4, "reuse stale h"; Section 4.1, persistent
+    combine buffer): the expert call scatters the refreshed rows into H_cache itself and the combine reads
+    every row from there.  Against the path through h_packed with write-through: y, H_cache and S_cache
+    bit for bit over two steps and five policies, and h_packed never written."""
+    li, _ = G.pick_layer(cfg, T=T)
+    c = li.cfg
+    dtype, k = c.dtype, c.k
+    Tn = li.x.shape[0]
+    say(f"rows to cache: config {cfg} T={Tn}")
+    ctx = B.Context(Tn, c.d, c.F, c.E, k, dtype)
+    dev = lambda a: G.to_dev(a, dtype)
+    args = (dev(li.Wg), G.f32_dev(li.bg) if li.bg is not None else None, dev(li.W1), None, dev(li.W2), None)
+    x0, x1 = dev(li.x), dev(WL.next_step_x(cfg, li.x))
+    pols = [B.Policy(B.REFRESH_ALG4, step_t=1, stride_n=2), B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=Tn // 3),
+            B.Policy(B.REFRESH_FRACTION_PAIR, n_units=Tn + Tn // 4), B.Policy(B.REFRESH_NONE),
+            B.Policy(B.REFRESH_FRACTION_TOKEN, n_units=Tn // 2, use_fresh_scores=True)]
+    for pol in pols:
+        out = {}
+        for direct in (False, True):
+            buf = B.LayerBuffers(ctx, G.DEV, with_cache=True)
+            poison(buf.h_packed)
+            y0 = B.moe_layer_forward(ctx, buf, x0, *args, policy=B.Policy(B.REFRESH_ALL), rows_to_cache=direct).clone()
+            y1 = B.moe_layer_forward(ctx, buf, x1, *args, policy=pol, rows_to_cache=direct).clone()
+            torch.cuda.synchronize()
+            ctx.moe_expert_ffn_status(buf.workspace)
+            if direct:
+                assert torch.isnan(buf.h_packed).all()          # the packed output buffer is not used at all
+            out[direct] = (y0, y1, buf.H_cache.clone(), buf.S_cache.clone())
+        for a, b_, name in zip(out[False], out[True], ("y step 0", "y step 1", "H_cache", "S_cache")):
+            assert torch.equal(a, b_), f"{name} differs under {pol}"
