@@ -344,10 +344,11 @@ static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bia
 // matrix pipe fed from hand-scheduled wavefronts, and wins as soon as its tiles fill most of the chip:
 //   256 x 192, one workgroup of eight wavefronts (4 x 2, each a 64 x 96 block; two per SIMD cover each
 //     other's waits, +1 % over four wavefronts of 128 x 96) per compute unit, two stages of activations
-//     and three of weights (136 KB of LDS): the GEMM with the plain epilogue, when that grid covers most
-//     of the 256 compute units.
-//     The weights stream from HBM exactly once; with a third stage each weight load has two steps of
-//     flight and the cold-weight penalty disappears (102 -> 88 us for GEMM2 at the DiT-MoE-XL shape);
+//     and four of weights (all 160 KB of LDS; three with short reductions): the GEMM with the plain
+//     epilogue, when that grid covers most of the 256 compute units.
+//     The weights stream from HBM exactly once, and a barrier waits for the slowest of a step's loads:
+//     every weight stage more gives those loads another step of flight (DiT-MoE-XL shape, GEMM2, same
+//     box: 98 us with two weight stages, 86 - 91 with three, 82 - 86 with four);
 //   128 x 192, two stages (80 KB of LDS), two workgroups per compute unit: the GEMM whose epilogue
 //     evaluates GELU (one workgroup's MFMAs cover the other's epilogue arithmetic), and GEMMs between
 //     one and two 256-wide rounds;
@@ -397,6 +398,8 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
         }
     }
     if (!GELU && fits_192 && tiles(256, 192) * 10 >= kComputeUnits * 6) {
+        if (K >= 320)      // four weight stages (all 160 KB of LDS): three steps of flight for the cold weight stream
+            return launch_gemm_bf16_wide<2, 3, 2, 2, 4, GELU, 4, 2>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
         if (K >= 256)
             return launch_gemm_bf16_wide<2, 3, 2, 2, 3, GELU, 4, 2>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
         return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
@@ -416,6 +419,7 @@ static hipError_t configure_gemm_bf16_auto()
 {
     hipError_t err = configure_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>();
     if (err == hipSuccess) err = configure_gemm_bf16_wide<2, 3, 2, 2, 3, GELU, 4, 2>();
+    if (err == hipSuccess) err = configure_gemm_bf16_wide<2, 3, 2, 2, 4, GELU, 4, 2>();
     if (err == hipSuccess) err = configure_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>();
     if (err == hipSuccess) err = configure_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>();
     return err;

@@ -59,8 +59,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
     constexpr int GROUP_M = 8;
     constexpr int REGION = epilogue_region_bytes<TN>();
     static_assert(NW * REGION <= AST * ABYTES + WST * WBYTES, "epilogue slabs must fit in the stage buffers");
-    static_assert((AST == 2 && (WST == 2 || WST == 3)) || (AST == 3 && WST == 3) || (AST == 4 && WST == 4),
-                  "ring depths (A, W): (2,2), (2,3), (3,3), (4,4)");
+    static_assert((AST == 2 && (WST == 2 || WST == 3 || WST == 4)) || (AST == 3 && WST == 3) || (AST == 4 && WST == 4),
+                  "ring depths (A, W): (2,2), (2,3), (2,4), (3,3), (4,4)");
     static_assert(NMFMA >= NFRAG, "one fragment read per MFMA slot");
     static_assert(SPREAD >= 1 && SPREAD <= 4, "a refill is issued within the four slices before it is needed");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -335,6 +335,18 @@ __global__ __launch_bounds__(64 * WGM * WGN, wide_occupancy(TM, TN, AST, WST, WG
             step(live_tag, kt, sa, sw, yes, pw, yes, no, yes, yes); advance(); ++kt;      // kt = nk-3: A(nk-1) is the last refill
             step(live_tag, kt, sa, sw, yes, p0, no, no, yes, no); advance(); ++kt;        // kt = nk-2
             step(live_tag, kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
+        } else if (AST == 2 && WST == 4) {
+            // as (2,3) with one more weight stage in flight: at the barrier of step kt the youngest load still
+            // needed is the A part of the previous refill, and only that refill's W part is younger
+            const std::integral_constant<int, QB> pw{};
+            step(live_tag, 0, 0, 0, yes, p0, yes, yes, no, no);
+            advance();
+            int kt = 1;
+            for (; kt + 4 < nk; ++kt) { step(live_tag, kt, sa, sw, yes, pw, yes, yes, yes, yes); advance(); }
+            step(live_tag, kt, sa, sw, yes, pw, yes, no, yes, yes); advance(); ++kt;      // kt = nk-4: W(nk-1) went with the refill before
+            step(live_tag, kt, sa, sw, yes, p0, yes, no, yes, no); advance(); ++kt;       // kt = nk-3: A(nk-1) is the last refill
+            step(live_tag, kt, sa, sw, yes, p0, no, no, yes, no); advance(); ++kt;        // kt = nk-2
+            step(live_tag, kt, sa, sw, no, p0, no, no, no, no);                           // kt = nk-1
         } else if (AST == 4 && WST == 4) {
             // three stages in flight per operand.  Loads younger than stage kt+1 at the barrier of step kt:
             // step 0: A2, A3 of the prologue; step 1: A3 and refill 0; later: the last two refills
@@ -444,7 +456,7 @@ static hipError_t launch_gemm_bf16_wide(const void* A, const void* W, const floa
     if (k_splits < 1 || (k_splits > 1 && (!partial || GELU))) return hipErrorInvalidValue;
     const int nk_min = K / 64 / k_splits;                         // steps of the smallest share
     if (WST == 3 && nk_min < 4) return hipErrorInvalidValue;      // the three-deep loops are written for at least four steps
-    if (WST == 4 && nk_min < 7) return hipErrorInvalidValue;      // the four-deep loop for at least seven
+    if (WST == 4 && nk_min < (AST == 4 ? 7 : 5)) return hipErrorInvalidValue;      // the four-deep loops: at least seven (five) steps
     if (nk_min < 1) return hipErrorInvalidValue;
     const int n_tiles_n = (N + BN - 1) / BN;
     const int m_tiles = (max_rows + BM - 1) / BM + n_seg;

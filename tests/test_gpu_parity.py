@@ -279,6 +279,11 @@ WIDE_FFN_CASES = [
     ("k-192", [900, 411, 1200, 777], 192, 1536),
     ("k-256", [900, 411, 1200, 777], 256, 1536),
     ("k-256-few-rows", [90, 41, 300, 77], 256, 4608),                             # three stages at four steps
+    # second GEMM on 256 x 192 tiles with the shortest reductions its four-deep weight ring takes (five and
+    # six 64-deep steps), and one step less (three-deep ring)
+    ("k2-320", [1391, 612, 1204, 893, 1347, 701, 1120, 924], 1152, 320),
+    ("k2-384", [1391, 612, 1204, 893, 1347, 701, 1120, 924], 1152, 384),
+    ("k2-256", [1391, 612, 1204, 893, 1347, 701, 1120, 924], 1152, 256),
     # tile-to-XCD dealing: one hot expert whose tiles spill over to the other XCDs' spare slots; many
     # segments that share five experts (three XCDs own nothing); more segments than a wavefront has
     # lanes (row-band order instead); sixteen experts, two per XCD
