@@ -1041,3 +1041,42 @@ def test_expert_rows_written_straight_into_the_cache_give_the_same_bits(cfg, T):
             out[direct] = (y0, y1, buf.H_cache.clone(), buf.S_cache.clone())
         for a, b_, name in zip(out[False], out[True], ("y step 0", "y step 1", "H_cache", "S_cache")):
             assert torch.equal(a, b_), f"{name} differs under {pol}"
+
+
+def test_measurement_aids_run_and_do_what_they_say():
+    """The library's calibration kernels and the between-GEMMs event (measurement aids of the C-ABI): the
+    copy is exact, the MFMA loop runs, and the event recorded between the two GEMMs of an expert FFN call
+    splits the call's time into two positive parts that add up to the whole."""
+    src = torch.arange(1 << 22, dtype=torch.int32, device=G.DEV)
+    dst = torch.zeros_like(src)
+    B.moe_calibrate_copy(dst, src, 512)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    ops = torch.randn(16 * 256 * 48, device=G.DEV).to(torch.bfloat16)
+    sink = torch.zeros(4, dtype=torch.float32, device=G.DEV)
+    B.moe_calibrate_mfma(ops, sink, 64, 32)
+    torch.cuda.synchronize()
+    assert (sink == 0).all()
+
+    d, F, rows = 256, 512, 2048
+    _, _, _, W1, b1, W2, b2 = G.small_inputs(93, 4, d, 2, F, "bf16", bias=False)
+    ctx = B.Context(rows, d, F, 2, 1, "bf16")
+    xp = torch.zeros((rows, d), dtype=torch.bfloat16, device=G.DEV)
+    h = torch.empty((rows, d), dtype=torch.bfloat16, device=G.DEV)
+    ws = torch.empty(ctx.workspace_bytes(), dtype=torch.uint8, device=G.DEV)
+    so = G.i32_dev(np.array([0, 1000, rows]))
+    se = torch.arange(2, dtype=torch.int32, device=G.DEV)
+    e0, em, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    em.record()
+    ctx.moe_expert_ffn_between_event(em)
+    e0.record()
+    ctx.moe_expert_ffn(xp, so, se, rows, G.to_dev(W1, "bf16"), None, G.to_dev(W2, "bf16"), None, h, ws)
+    e1.record()
+    ctx.moe_expert_ffn_between_event(None)
+    torch.cuda.synchronize()
+    a, b_, whole = e0.elapsed_time(em), em.elapsed_time(e1), e0.elapsed_time(e1)
+    assert a > 0 and b_ > 0 and abs(a + b_ - whole) < 0.05 * whole + 1e-3
+    # and once the hook is removed the event is left alone
+    ctx.moe_expert_ffn(xp, so, se, rows, G.to_dev(W1, "bf16"), None, G.to_dev(W2, "bf16"), None, h, ws)
+    torch.cuda.synchronize()
+    assert abs(e0.elapsed_time(em) - a) < 1e-6
