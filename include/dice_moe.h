@@ -173,7 +173,7 @@ int moe_policy_refreshed_pairs(moe_ctx* ctx, const moe_policy* policy, int32_t T
  *        inv[T*k]: packed row of pair p, -1 if p is not refreshed.
  * x_packed may be NULL: then only the index outputs are written (x is not read and may be NULL too)
  * and the rows are gathered by the consumer, see moe_expert_ffn_rows.
- * workspace: moe_workspace_bytes(); at most the first 4 * (E + n_shared) * ceil(T*k / 256) bytes carry
+ * workspace: moe_workspace_bytes(); at most the first 4 * (E + n_shared) * (ceil(T*k / 256) + 1) bytes carry
  * per-workgroup expert counts between the two launches of the sort (they overlap the expert FFN's
  * hidden activations: calls that share a workspace must run in stream order).  NULL is accepted
  * when T*k <= 2048 (one workgroup sorts alone). */
@@ -185,7 +185,8 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* expert_idx, const u
  * tight serving loops, harnesses that forbid hipMalloc.  The per-workgroup counts that moe_dispatch
  * keeps in the caller's workspace live here in a 64 KiB array inside the library's device code (one
  * per GPU, held until the process ends); the call allocates nothing and returns the same outputs,
- * bit for bit.  Limit: 4 * (E + n_shared) * ceil(T*k / 256) <= 65536 bytes (e.g. E = 8: up to 2^19
+ * bit for bit.  Limit: 4 * (E + n_shared) * (workgroups + 1) <= 65536 bytes, where the sort runs on at
+ * most 256 workgroups up to 2^19 pairs and on ceil(T*k / 2048) beyond (e.g. E = 8: up to 4 million
  * pairs); beyond it the call returns MOE_ERR_SHAPE and launches nothing.  Every call on a GPU shares
  * that GPU's array: calls that overlap on one GPU (two streams, two threads) race; calls in stream
  * order are safe, and nothing in the array has to be cleared between them (the counting launch writes

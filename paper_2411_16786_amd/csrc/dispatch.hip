@@ -8,7 +8,8 @@
 // stable by construction.
 //   dispatch_count_kernel: per-workgroup, per-expert counts of refreshed pairs -> scratch[b][e].
 //   dispatch_place_kernel: every workgroup sums the scratch table into the experts' totals and
-//     into the counts of the workgroups before it, scans the totals into the experts' offsets,
+//     into the counts of the workgroups before it (grids beyond 256 workgroups: dispatch_scan_kernel
+//     has done that once for all of them), scans the totals into the experts' offsets,
 //     ranks its own pairs (lanes that hold the same expert find each other with one ballot per bit
 //     of the expert id; per-wave, per-expert running counts in LDS), and writes perm / inv.
 //     With a single workgroup the table is not needed and the count kernel is not launched.
@@ -106,11 +107,41 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_count_kernel(const int32
     if (tid < E) block_counts[static_cast<size_t>(blockIdx.x) * E + tid] = cnt[tid];
 }
 
+// Grids beyond 256 workgroups: one workgroup turns the table of per-workgroup counts into exclusive
+// prefixes over the workgroups (row b: pairs of each expert in the workgroups before b) and appends the
+// totals as row n_blocks, so that every placing workgroup reads two rows instead of the whole table.
+// Wave w takes experts w, w + 16, ...; lane l of it owns a contiguous run of workgroups.
+__global__ __launch_bounds__(1024) void dispatch_scan_kernel(int32_t* __restrict__ block_counts, int n_blocks, int E)
+{
+    const int wave = threadIdx.x / kWave;
+    const int lane = lane_id();
+    const int per_lane = (n_blocks + kWave - 1) / kWave;
+    const int b_lo = lane * per_lane;
+    const int b_hi = (b_lo + per_lane < n_blocks) ? b_lo + per_lane : n_blocks;
+    for (int e = wave; e < E; e += 1024 / kWave) {
+        int run = 0;
+        for (int bb = b_lo; bb < b_hi; ++bb) run += block_counts[static_cast<size_t>(bb) * E + e];
+        int incl = run;                           // inclusive scan of the lanes' sums
+#pragma unroll
+        for (int sh = 1; sh < kWave; sh <<= 1) {
+            const int v = __shfl_up(incl, sh, kWave);
+            if (lane >= sh) incl += v;
+        }
+        int prefix = incl - run;
+        for (int bb = b_lo; bb < b_hi; ++bb) {
+            const int c = block_counts[static_cast<size_t>(bb) * E + e];
+            block_counts[static_cast<size_t>(bb) * E + e] = prefix;
+            prefix += c;
+        }
+        if (lane == kWave - 1) block_counts[static_cast<size_t>(n_blocks) * E + e] = incl;
+    }
+}
+
 template <int S>
 __global__ __launch_bounds__(kIdxThreads) void dispatch_place_kernel(const int32_t* __restrict__ expert_idx,
                                                                     const uint8_t* __restrict__ mask, int N, int E,
                                                                     const int32_t* __restrict__ block_counts,
-                                                                    int32_t* __restrict__ counts,
+                                                                    int prefix_ready, int32_t* __restrict__ counts,
                                                                     int32_t* __restrict__ offsets,
                                                                     int32_t* __restrict__ perm,
                                                                     int32_t* __restrict__ inv)
@@ -129,8 +160,15 @@ __global__ __launch_bounds__(kIdxThreads) void dispatch_place_kernel(const int32
     if (tid < kMaxExperts) { s_tot[tid] = 0; s_pre[tid] = 0; }
     __syncthreads();
 
-    // the table of the other workgroups' counts: totals, and the part that precedes this workgroup
-    if (n_blocks > 1) {
+    // the table of the other workgroups' counts: totals, and the part that precedes this workgroup.  Large
+    // grids (prefix_ready) find both already summed by dispatch_scan_kernel: row b holds the counts of the
+    // workgroups before b, row n_blocks the totals.
+    if (n_blocks > 1 && prefix_ready) {
+        if (tid < E) {
+            s_pre[tid] = block_counts[static_cast<size_t>(b) * E + tid];
+            s_tot[tid] = block_counts[static_cast<size_t>(n_blocks) * E + tid];
+        }
+    } else if (n_blocks > 1) {
         for (int i = tid; i < n_blocks * E; i += kIdxThreads) {
             const int c = block_counts[i];
             const int bb = i / E, e = i - bb * E;
@@ -297,17 +335,20 @@ size_t dispatch_scratch_bytes(long long n_pairs, int E)
 {
     int steps, blocks;
     dispatch_plan(n_pairs, steps, blocks);
-    return blocks > 1 ? static_cast<size_t>(blocks) * E * sizeof(int32_t) : 0;
+    return blocks > 1 ? static_cast<size_t>(blocks + 1) * E * sizeof(int32_t) : 0;      // one row per workgroup, and the totals
 }
 
 template <int S>
 static void launch_dispatch_index(const int32_t* idx, const uint8_t* mask, int N, int E, int blocks, int32_t* scratch,
                                   int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv, hipStream_t stream)
 {
+    const int scan = blocks > 256 ? 1 : 0;      // small grids: every placing workgroup sums the table itself
     if (blocks > 1)
         hipLaunchKernelGGL(dispatch_count_kernel<S>, dim3(blocks), dim3(kIdxThreads), 0, stream, idx, mask, N, E, scratch);
+    if (scan)
+        hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), 0, stream, scratch, blocks, E);
     hipLaunchKernelGGL(dispatch_place_kernel<S>, dim3(blocks), dim3(kIdxThreads), 0, stream, idx, mask, N, E, scratch,
-                       counts, offsets, perm, inv);
+                       scan, counts, offsets, perm, inv);
 }
 
 hipError_t launch_dispatch(bool bf16, const void* x, const int32_t* idx, const uint8_t* mask, int T_tok, int d,

@@ -185,6 +185,7 @@ def test_refresh_mask_bit_exact(T, k):
     (70000, 64, 2, 64, "bf16", True),
     (150000, 8, 2, 64, "bf16", False),
     (300000, 5, 2, 64, "bf16", True),
+    (400000, 64, 3, 64, "bf16", True),          # 586 workgroups, 64 experts: the scan kernel between count and place
 ])
 def test_dispatch_bit_exact(T, E, k, d, dtype, masked):
     say(f"dispatch T={T} E={E} k={k} d={d} {dtype} masked={masked}")
