@@ -67,9 +67,9 @@ def main():
                          "whose results the next step collects on a second stream.  dice = the paper's combination: interweaved "
                          "in the shallow half of the layers, synchronous in the deep half (Selective Synchronization), "
                          "Algorithm 4 with stride 2 in every layer (Conditional Communication); launched eagerly")
-    ap.add_argument("--workload", choices=["xl", "g"], default="xl",
+    ap.add_argument("--workload", choices=["xl", "g", "s"], default="xl",
                     help="xl: DiT-MoE-XL shape x 28 layers (the headline workload); g: DiT-MoE-G shape (16 experts, "
-                         "d=1792) x 40 layers")
+                         "d=1792) x 40 layers; s: the small DiT-MoE-S-shaped layer (T=2048, d=384, 16 experts) x 12 layers")
     ap.add_argument("--tokens", type=int, default=None,
                     help="tokens per layer call instead of the workload's (smaller local batches; not the headline)")
     ap.add_argument("--eager", action="store_true", help="launch from Python every step instead of replaying a HIP graph")
@@ -87,9 +87,9 @@ def main():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
     dev = "cuda"
-    wl_cfg = 3 if args.workload == "xl" else 6
+    wl_cfg = {"xl": 3, "g": 6, "s": 2}[args.workload]
     c = WL.CONFIGS[wl_cfg]
-    n_layers = args.layers or c.layers
+    n_layers = args.layers or (12 if args.workload == "s" else c.layers)
     T, d, E, k, F = (args.tokens or c.T), c.d, c.E, c.k, c.F
     n_shared = args.n_shared
     N = T * (k + n_shared)          # (token, slot) pairs: k routed slots and one per shared expert
@@ -111,8 +111,8 @@ def main():
                                   range(first, min(first + 8, n_layers))))
             for li in chunk:
                 buf = B.LayerBuffers(ctx, dev, workspace=workspace)
-                layers.append(dict(x=up(li.x), Wg=up(li.Wg), bg=torch.from_numpy(li.bg).to(dev), W1=up(li.W1),
-                                   W2=up(li.W2), buf=buf))
+                layers.append(dict(x=up(li.x), Wg=up(li.Wg), bg=None if li.bg is None else torch.from_numpy(li.bg).to(dev),
+                                   W1=up(li.W1), W2=up(li.W2), buf=buf))
             if first == 0:
                 cpu_layers = chunk[:n_cpu]
             del chunk
@@ -526,7 +526,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": ("configs[2]: DiT-MoE-XL-shaped layer x 28 (T=4096, d=1152, E=8, top-2, F=4608)"
                                 if args.workload == "xl" else
-                                f"DiT-MoE-G-shaped layer x {c.layers} (T={T}, d={d}, E={E}, top-{k}, F={F})")
+                                f"{'DiT-MoE-G' if args.workload == 'g' else 'configs[1]: DiT-MoE-S'}-shaped layer x {n_layers} "
+                                f"(T={T}, d={d}, E={E}, top-{k}, F={F})")
                                + (f" + {n_shared} shared experts per layer" if n_shared else ""),
                    "layers": n_layers, "tokens": T, "launch": "eager" if graph is None else "hipGraph replay",
                    "refresh": ("full (synchronous layer)" if args.schedule != "dice" else

@@ -352,8 +352,8 @@ static hipError_t launch_gemm_f32(const void* A, const void* W, const float* bia
 //   128 x 192, two stages (80 KB of LDS), two workgroups per compute unit: the GEMM whose epilogue
 //     evaluates GELU (one workgroup's MFMAs cover the other's epilogue arithmetic), and GEMMs between
 //     one and two 256-wide rounds;
-//   128 x 192, three stages, one workgroup per compute unit: grids of at most one workgroup per compute
-//     unit (few refreshed rows).  Alone on a compute unit a workgroup has nobody to hide its load
+//   128 x 192, three stages, one workgroup per compute unit: grids of a quarter to one workgroup per
+//     compute unit (few refreshed rows, or narrow outputs).  Alone on a compute unit a workgroup has nobody to hide its load
 //     latency, and the third stage gives every load two steps of flight instead of one
 //     (57 us instead of 78 us for GEMM2 at 4096 rows of the DiT-MoE-XL widths).
 // Tiny problems stay on the 128 x 128 kernel, three workgroups per compute unit.
@@ -378,12 +378,14 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
     // the 128 x 192 tiles do not fill the chip and each walks all of K.  With two or three workgroups per
     // tile, each on a share of K (float partial sums in the workspace, added by a second pass in a fixed
     // order), more compute units stream the weights at once: 54 -> 47 us at 2048 rows of the DiT-MoE-XL
-    // widths.  Not worth it once the tiles fill the chip by themselves (57 vs 66 us at 4096 rows).
+    // widths.  Not worth it once the tiles fill the chip by themselves (57 vs 66 us at 4096 rows), nor when a
+    // share is left with fewer than sixteen steps (DiT-MoE-S widths, K = 1536, 4096 rows: 32 us split in
+    // three, 23 in two, 20 unsplit on three-stage tiles): the second pass then costs more than the split saves.
     if (!GELU && partial && fits_192 && by_expert) {
         const long long t23 = tiles(128, 192);
         int splits = 1;
         for (int sp = 3; sp >= 2 && splits == 1; --sp)       // the deepest split whose shares still fill the chip at most once
-            if (t23 * sp * 20 <= kComputeUnits * 21 && K / 64 / sp >= 8 &&
+            if (t23 * sp * 20 <= kComputeUnits * 21 && K / 64 / sp >= 16 &&
                 static_cast<size_t>(sp) * max_rows * N * sizeof(float) <= partial_bytes)
                 splits = sp;
         if (splits > 1) {
@@ -404,7 +406,7 @@ static hipError_t launch_gemm_bf16_auto(const void* A, const void* W, const floa
             return launch_gemm_bf16_wide<2, 3, 2, 2, 3, GELU, 4, 2>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
         return launch_gemm_bf16_wide<4, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
     }
-    if (fits_192 && K >= 256 && tiles(128, 192) <= kComputeUnits && tiles(128, 192) * 2 >= kComputeUnits)
+    if (fits_192 && K >= 256 && tiles(128, 192) <= kComputeUnits && tiles(128, 192) * 4 >= kComputeUnits)
         return launch_gemm_bf16_wide<2, 3, 2, 3, 3, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
     if (fits_192 && tiles(128, 192) * 2 >= kComputeUnits)
         return launch_gemm_bf16_wide<2, 3, 2, 2, 2, GELU>(A, W, bias, C, N, K, seg_offsets, seg_expert, n_seg, max_rows, stream, row_index, row_div, out_index, by_expert, nullptr, 1, status);
