@@ -339,6 +339,27 @@ def main():
             flops = 2.0 * 32 * 32 * 16 * 8 * iters * 4 * wgs
             calibration["mfma"].append({"operands": name, "us": round(ms * 1e3, 1),
                                         "TFLOP/s": round(flops / (ms * 1e-3) / 1e12, 1)})
+        # yardstick only: the vendor library's plain bf16 GEMM (through torch.matmul) at the two dense shapes of
+        # this workload's FFN, i.e. one even segment, no gather, bias or GELU, the same operands every call
+        rows = T * k
+        calibration["library_gemm"] = []
+        for name, n_, k_ in (("rows x F x d (the first GEMM's shape)", F, d), ("rows x d x F (the second GEMM's shape)", d, F)):
+            a_ = torch.randn(rows, k_, device=dev).to(torch.bfloat16)
+            w_ = (torch.randn(n_, k_, device=dev) * 0.02).to(torch.bfloat16)
+            out_ = torch.empty(rows, n_, dtype=torch.bfloat16, device=dev)
+            for _ in range(3):
+                torch.matmul(a_, w_.t(), out=out_)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(20):
+                torch.matmul(a_, w_.t(), out=out_)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 20
+            calibration["library_gemm"].append({"shape": name, "rows": rows, "us": round(us, 1),
+                                                "TFLOP/s": round(2.0 * rows * n_ * k_ / us * 1e-6, 1)})
+            del a_, w_, out_
 
     # ---- Conditional Communication at the 512px shape (two consecutive diffusion steps), weights of the 28 layers
     cond = None
